@@ -1,0 +1,232 @@
+/*
+ * semipd.h - C ABI of the semi-PD hot path on one MI355X (gfx950).
+ *
+ * What the library is: the prefill worker's and the decode worker's attention
+ * step, running at the same time on disjoint sets of compute units of ONE GPU,
+ * over ONE paged KV-cache pool shared by both (paper: System Design, "Overview",
+ * "Prefill and Decode Workers", "Computational Resource Controller", "Unified
+ * Memory Manager").  The paper partitions SMs between two processes with MPS;
+ * here the two phases are two HIP streams created with disjoint CU masks.
+ *
+ * Conventions
+ *  - Every call returns an int status (SPD_OK or a negative SPD_E*), never throws,
+ *    and leaves all library state unchanged when it fails.
+ *  - "device" pointers are HIP device addresses owned by the caller (the library
+ *    never frees them); "host" pointers are ordinary host memory read during the
+ *    call only.  Tensors are dense row-major bf16 unless stated otherwise.
+ *  - Steps are asynchronous: they enqueue work on the calling phase's current
+ *    stream and return.  Use spd_phase_sync / spd_phase_query to wait.
+ *  - One thread may drive the prefill phase while another drives the decode
+ *    phase (the paper's two asynchronous workers).  spd_kv_* may be called from
+ *    both at once.  Two threads must not drive the SAME phase concurrently.
+ */
+#ifndef SEMIPD_H
+#define SEMIPD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct spd_ctx spd_ctx;   /* device, partition state, per-phase streams and staging   */
+typedef struct spd_pool spd_pool; /* unified KV pool: pages + allocator + block tables        */
+
+enum {
+  SPD_OK = 0,
+  SPD_EINVAL = -1, /* bad argument (null pointer, non-positive size, unsupported shape)     */
+  SPD_ENOMEM = -2, /* pool exhausted: fewer free blocks than the call needs                 */
+  SPD_ENOENT = -3, /* unknown request id                                                    */
+  SPD_EHIP = -5,   /* a HIP call failed; spd_last_hip_error() has its code                  */
+  SPD_ESTATE = -6  /* call not valid in this state (e.g. a step on a host-only context)     */
+};
+
+enum { SPD_PHASE_PREFILL = 0, SPD_PHASE_DECODE = 1 };
+
+typedef enum { SPD_KV_GQA = 0, SPD_KV_MLA_LATENT = 1 } spd_kv_kind;
+
+/* ------------------------------------------------------------------ context */
+
+/* Create a context on HIP device `device` (>= 0).  device == -1 creates a host-only
+ * context: allocator, block tables and the partition state machine work, no GPU is
+ * touched, and every call that would launch work returns SPD_ESTATE.
+ * The initial partition is (all CUs, all CUs): both phases may use the whole chip,
+ * the paper's (100, 100) setting ("Computational Resource Controller"). */
+int spd_ctx_create(int device, spd_ctx** out);
+int spd_ctx_destroy(spd_ctx* ctx);
+
+/* CU count, XCD count and the granularity (in CUs) to which partition sizes are rounded
+ * (one CU in every XCD).  A host-only context reports MI355X's 256 / 8 / 8. */
+int spd_device_info(spd_ctx* ctx, int* total_cus, int* xcds, int* cu_granularity);
+
+/* ------------------------------------------------------------------ unified KV pool
+ * Paper: "Unified Memory Manager" - one paged store for the KV cache of both workers,
+ * accessed through per-request block tables.  The pool memory belongs to the caller
+ * and must outlive the pool object; it survives every spd_set_partition (the paper's
+ * resident process that keeps weights and KV cache across worker switches).
+ *
+ * Page geometry.  GQA: a page holds page_tokens tokens of K [n_kv_heads, dim_k] and
+ * V [n_kv_heads, dim_v]; page_tokens must be a multiple of 16; dim_k == dim_v in {64, 128}.
+ * MLA latent: a page holds page_tokens rows of dim_k (= 576) values, n_kv_heads = 1,
+ * dim_v = 512 is the number of leading dims that act as values; page_tokens % 16 == 0.
+ * The byte layout inside a page is private to the library (it is arranged for the
+ * decode kernel's matrix-core operand order); read or write pages only through
+ * spd_kv_write / spd_kv_gather / the steps. */
+typedef struct {
+  int32_t kind;        /* spd_kv_kind */
+  int32_t page_tokens; /* P */
+  int32_t n_kv_heads;
+  int32_t dim_k;
+  int32_t dim_v;
+  int64_t num_pages;
+} spd_pool_desc;
+
+/* Bytes a pool of this geometry needs. */
+int spd_pool_bytes(const spd_pool_desc* desc, uint64_t* bytes_out);
+/* dev_mem: device pointer, 256-byte aligned, `bytes` >= spd_pool_bytes.  With a host-only
+ * context dev_mem may be NULL.  The pool starts with every page free. */
+int spd_pool_create(spd_ctx* ctx, void* dev_mem, uint64_t bytes, const spd_pool_desc* desc, spd_pool** out);
+int spd_pool_destroy(spd_pool* pool);
+/* total pages, free pages, live requests, number of successful mutating operations so far. */
+int spd_pool_stats(spd_pool* pool, int64_t* total, int64_t* free_pages, int64_t* live_reqs, uint64_t* op_seq);
+
+/* Atomic block allocation (paper: "Unified Memory Manager", the query / get / update of the
+ * memory utilisation done under one lock so that the two asynchronous workers cannot
+ * interleave).  Thread-safe.  Policy (the paper fixes none; this is the library's contract):
+ * the free list is a stack whose first pops are 0, 1, 2, ...; reserve grows request `req_id`'s
+ * block table to ceil(n_tokens_total / P) blocks (creating the request if new; never shrinks);
+ * all-or-nothing: SPD_ENOMEM and no change if too few blocks are free.  free returns every
+ * block of the request, pushed back last-to-first, and forgets the request.
+ * op_seq_out (nullable) receives the operation's position (1, 2, ...) in the pool's
+ * linearised order of successful mutating calls; failed calls consume no number. */
+int spd_kv_reserve(spd_pool* pool, uint64_t req_id, int32_t n_tokens_total, uint64_t* op_seq_out);
+int spd_kv_free(spd_pool* pool, uint64_t req_id, uint64_t* op_seq_out);
+/* Copy the request's block table (physical page ids, logical order) to host `out[cap]`;
+ * *n_out = its length (also when cap is too small, in which case SPD_EINVAL is returned). */
+int spd_kv_block_table(spd_pool* pool, uint64_t req_id, int32_t* out, int32_t cap, int32_t* n_out);
+/* Copy the free stack, bottom to top (the next reserve pops out[n-1]), to host `out[cap]`. */
+int spd_kv_free_list(spd_pool* pool, int32_t* out, int64_t cap, int64_t* n_out);
+
+/* Write n_tokens rows into request `req_id`'s pages at logical positions
+ * [start_pos, start_pos + n_tokens); blocks must already be reserved (SPD_EINVAL if not).
+ * GQA: k device [n_tokens, n_kv_heads, dim_k], v device [n_tokens, n_kv_heads, dim_v].
+ * MLA: k device [n_tokens, dim_k] latent rows, v must be NULL.
+ * Enqueued on `phase`'s current stream (paper, "Prefill and Decode Workers": the K, V
+ * projections of a request are written into the KV cache). */
+int spd_kv_write(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int32_t start_pos,
+                 int32_t n_tokens, const void* k, const void* v);
+/* Inverse of spd_kv_write: logical rows [0, n_tokens) of the request to dense device
+ * buffers of the same shapes (v_out NULL for MLA).  For tests and migration. */
+int spd_kv_gather(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int32_t n_tokens,
+                  void* k_out, void* v_out);
+
+/* ------------------------------------------------------------------ the two steps */
+
+/* Prefill step (paper, Background "LLM Processing Phases" and "Prefill and Decode
+ * Workers": the prefill iteration processes the whole prompt and writes its K, V into the
+ * cache).  For each request r (rows cu_seqlens[r] .. cu_seqlens[r+1] of the packed batch) and
+ * query head h (KV head h / (n_q_heads / n_kv_heads)):
+ *     out[i, h, :] = sum_{j <= i} softmax_j(scale * q[i, h, :] . k[j, g, :]) * v[j, g, :]
+ * and the request's rows are written to its pages at positions 0 .. len-1; the step reserves
+ * ceil(len / P) blocks per request first (all requests or none: SPD_ENOMEM changes nothing).
+ *   q   device [T, n_q_heads, dim_qk]    k device [T, n_kv_heads, dim_qk]
+ *   v   device [T, n_kv_heads, dim_v]    out device [T, n_q_heads, dim_v]
+ * GQA pool: n_kv_heads / dim_qk / dim_v are the pool's.  MLA pool: k, v are the un-absorbed
+ * per-head tensors (n_kv_heads == n_q_heads, dim_qk 192, dim_v 128) and `latent` device
+ * [T, 576] is what is written to the pages; latent must be NULL for a GQA pool.
+ * Zero-length requests are SPD_EINVAL; scale must be positive and finite (the running maximum
+ * of the scores is taken before scaling). */
+typedef struct {
+  int32_t n_req;
+  const uint64_t* req_ids;   /* host [n_req] */
+  const int32_t* cu_seqlens; /* host [n_req + 1], cu_seqlens[0] == 0 */
+  const void* q;
+  const void* k;
+  const void* v;
+  const void* latent;
+  void* out;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t dim_qk;
+  int32_t dim_v;
+  float scale;
+} spd_prefill_batch;
+int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_batch* batch);
+
+/* Decode step (paper, Background: the decode phase produces the next token from the last
+ * token and the KV cache, and appends the new key / value; "Unified Memory Manager": the
+ * cache is read through the block table, and the decode worker allocates inside the paged
+ * attention computation).  For each request b with context n = ctx_lens[b] >= 1 and head h:
+ *     out[b, h, :] = sum_{t < n} softmax_t(scale * q[b, h, :] . K_b[t, g, :]) * V_b[t, g, :]
+ * where K_b, V_b are the request's cached rows found through its block table.  If k_new is
+ * non-NULL the step first reserves blocks for n tokens and writes k_new[b], v_new[b] at
+ * position n - 1 (so n counts the token being decoded); if NULL it attends only.
+ *   GQA: q device [B, n_q_heads, dim_k], k_new/v_new device [B, n_kv_heads, dim_k/dim_v],
+ *        out device [B, n_q_heads, dim_v].
+ *   MLA: q device [B, n_q_heads, 576] (absorbed query), k_new device [B, 576] latent rows,
+ *        v_new NULL, out device [B, n_q_heads, 512];
+ *        s[h,t] = scale * q[b,h,:] . c_t,  out[b,h,:] = sum_t softmax_t(s[h,:]) * c_t[0:512].
+ * n_q_heads must be a multiple of n_kv_heads with at most 16 query heads per KV head; scale
+ * must be positive and finite. */
+typedef struct {
+  int32_t n_req;
+  const uint64_t* req_ids; /* host [n_req] */
+  const int32_t* ctx_lens; /* host [n_req] */
+  const void* q;
+  const void* k_new;
+  const void* v_new;
+  void* out;
+  int32_t n_q_heads;
+  float scale;
+} spd_decode_batch;
+int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* batch);
+
+/* Block the calling thread until everything enqueued so far by `phase` has finished. */
+int spd_phase_sync(spd_ctx* ctx, int phase);
+/* *done = 1 if everything enqueued so far by `phase` has finished, else 0.  Never blocks. */
+int spd_phase_query(spd_ctx* ctx, int phase, int* done);
+/* Make `phase`'s future work wait (on the GPU, not the host) for everything `other` has
+ * enqueued so far - e.g. a decode step that reads pages a prefill step has just written. */
+int spd_phase_wait_for(spd_ctx* ctx, int phase, int other);
+/* The phase's current hipStream_t, for callers that enqueue their own work or events. */
+int spd_phase_stream(spd_ctx* ctx, int phase, void** hip_stream_out);
+/* GPU time of the phase's most recent step in milliseconds (waits for that step). */
+int spd_phase_last_ms(spd_ctx* ctx, int phase, float* ms);
+
+/* ------------------------------------------------------------------ partition
+ * Paper, "Computational Resource Controller": a configuration (x, y) gives x % of the
+ * compute units to prefill and y % to decode; x + y may exceed 100 (the two then compete);
+ * a new (x, y) is prepared first and adopted late (delayed switching), and each worker
+ * adopts it at its own iteration boundary without waiting for the other (asynchronous
+ * switching).  Here (x, y) are CU counts.  Each is rounded to the nearest multiple of the
+ * granularity, at least one granule, at most all CUs.  Prefill takes CUs from the low end of
+ * the mask, decode from the high end; they overlap only when the counts sum above the total.
+ * The call prepares (creates or re-uses) the two CU-masked streams and stages them as
+ * pending; it never blocks on GPU work and never touches the pool.  Each phase switches to
+ * its pending stream at the start of its next step; the new stream waits on the GPU for the
+ * old stream's last work of that phase, so steps of one phase stay ordered. */
+int spd_set_partition(spd_ctx* ctx, int prefill_cus, int decode_cus);
+/* Active and pending CU counts per phase (pending == active when nothing is staged). */
+int spd_get_partition(spd_ctx* ctx, int* prefill_active, int* decode_active, int* prefill_pending,
+                      int* decode_pending);
+/* The CU mask (one bit per CU, 32 per word) of the phase's ACTIVE stream to host words[cap]. */
+int spd_phase_cu_mask(spd_ctx* ctx, int phase, uint32_t* words, int32_t cap, int32_t* n_words);
+/* Pure function: masks for a (prefill_cus, decode_cus) request on a device with total_cus CUs
+ * and the given granularity; writes ceil(total_cus / 32) words to each of host
+ * prefill_words / decode_words and the rounded counts to *p_out / *d_out. */
+int spd_partition_masks(int total_cus, int granularity, int prefill_cus, int decode_cus,
+                        uint32_t* prefill_words, uint32_t* decode_words, int* p_out, int* d_out);
+
+/* Debug aid: run a tiny kernel of `n_blocks` workgroups on the phase's current stream and
+ * report, to host ids[cap], the distinct hardware (XCD << 16 | SE << 8 | CU) ids that ran
+ * them; used to check that a masked stream stays on its CUs. */
+int spd_phase_probe_cus(spd_ctx* ctx, int phase, int32_t n_blocks, int32_t* ids, int32_t cap, int32_t* n_ids);
+
+const char* spd_strerror(int status);
+/* The hipError_t of the most recent SPD_EHIP on this thread (0 if none). */
+int spd_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEMIPD_H */

@@ -1,0 +1,150 @@
+// Internal declarations shared by the host side and the kernels of libsemipd.
+// Not part of the public ABI (see include/semipd.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <map>
+#include <mutex>
+#include <unordered_map>
+#include <vector>
+
+#include "semipd.h"
+
+namespace spd {
+
+// ---------------------------------------------------------------------------------------------
+// Page layout in HBM.
+//
+// Tokens are grouped in tiles of 16 (TILE_T).  A GQA page holds, for every KV head g, a
+// contiguous "head region" of P/16 tiles; each tile is a K part followed by a V part:
+//
+//   K part (16 tokens x dk):  [chunk c = d/8][token t][8 dims]
+//       A wave that loads "chunk 4s + lane/16, token lane%16" with one 16-byte load per lane
+//       reads 1 KiB contiguous and gets exactly the A operand of v_mfma_f32_16x16x32_bf16
+//       (row = token, 8 consecutive contraction elements per lane) for k-step s.
+//   V part (16 tokens x dv):  [d/32][token quad t/4][d%16][(d/16)%2][t%4]
+//       One 16-byte load per lane at "(blk2*4 + lane/16)*16 + lane%16" is again 1 KiB
+//       contiguous and holds the A operands (row = d, 4 consecutive tokens per lane) of two
+//       v_mfma_f32_16x16x16_bf16 for the value blocks 2*blk2 and 2*blk2 + 1.
+//
+// An MLA latent page holds P/16 tiles of 16 tokens x 576 dims in the K-part layout only.
+// ---------------------------------------------------------------------------------------------
+constexpr int TILE_T = 16;
+
+struct PoolGeom {
+  int kind, P, Hkv, dk, dv;
+  int tiles_per_page;
+  uint32_t tile_k_bytes, tile_v_bytes, tile_bytes, head_bytes;
+  uint64_t page_bytes;
+};
+
+__host__ __device__ inline uint32_t k_elem_offset(int t16, int d) { return ((d >> 3) * 16 + t16) * 8 + (d & 7); }
+__host__ __device__ inline uint32_t v_elem_offset(int t16, int d) {
+  return (((((d >> 5) * 4 + (t16 >> 2)) * 16 + (d & 15)) * 2 + ((d >> 4) & 1)) * 4) + (t16 & 3);
+}
+
+inline PoolGeom make_geom(const spd_pool_desc& d) {
+  PoolGeom g{};
+  g.kind = d.kind; g.P = d.page_tokens; g.Hkv = d.n_kv_heads; g.dk = d.dim_k; g.dv = d.dim_v;
+  g.tiles_per_page = d.page_tokens / TILE_T;
+  g.tile_k_bytes = TILE_T * d.dim_k * 2;
+  g.tile_v_bytes = d.kind == SPD_KV_GQA ? TILE_T * d.dim_v * 2 : 0;
+  g.tile_bytes = g.tile_k_bytes + g.tile_v_bytes;
+  g.head_bytes = g.tiles_per_page * g.tile_bytes;
+  g.page_bytes = (uint64_t)g.head_bytes * d.n_kv_heads;
+  return g;
+}
+
+// One 16-token tile's worth of rows to copy between a dense [rows, heads, dim] tensor and a page.
+struct TileDesc {
+  int32_t src_row;   // row of the dense tensor that maps to token t_begin of the tile
+  int32_t page;      // physical page id
+  int32_t sub;       // tile index inside the page
+  int32_t t_begin;   // first token slot (0..15) touched
+  int32_t t_end;     // one past the last token slot touched
+  int32_t pad[3];
+};
+
+// Prefill work item: one tile of BLOCK_M query rows of one request.
+struct PrefillWork {
+  int32_t row0;      // first packed row of the request
+  int32_t len;       // request length
+  int32_t q_tile;    // tile index inside the request
+  int32_t pad;
+};
+
+extern thread_local int g_last_hip_error;
+inline int hip_fail(hipError_t e) { g_last_hip_error = (int)e; return SPD_EHIP; }
+#define SPD_HIP(expr) do { hipError_t _e = (expr); if (_e != hipSuccess) return ::spd::hip_fail(_e); } while (0)
+
+}  // namespace spd
+
+// ------------------------------------------------------------------------------------------ objects
+struct spd_pool {
+  spd_ctx* ctx;
+  spd_pool_desc desc;
+  spd::PoolGeom geom;
+  char* base;
+  uint64_t bytes;
+  std::mutex mu;                                  // the "lock on memory utilisation"
+  std::vector<int32_t> free_stack;                // top = back()
+  int64_t used = 0;
+  uint64_t op_seq = 0;
+  std::unordered_map<uint64_t, std::vector<int32_t>> tables;
+};
+
+struct spd_stage {          // pinned host buffer + device twin, reused round-robin per phase
+  char* host = nullptr;
+  char* dev = nullptr;
+  size_t cap = 0;
+  hipEvent_t done = nullptr;
+  bool in_flight = false;
+};
+
+struct spd_phase_state {
+  hipStream_t stream = nullptr;        // active
+  int active_cus = 0;
+  hipStream_t pending_stream = nullptr;
+  int pending_cus = 0;
+  bool has_pending = false;
+  std::vector<uint32_t> active_mask, pending_mask;
+  spd_stage ring[4];
+  int ring_pos = 0;
+  hipEvent_t ev_start = nullptr, ev_end = nullptr, ev_switch = nullptr, ev_cross = nullptr;
+  bool timed = false;
+  char* workspace = nullptr;           // split-K partials (decode)
+  size_t ws_cap = 0;
+};
+
+struct spd_ctx {
+  int device = -1;                     // -1: host only
+  int total_cus = 256, xcds = 8, granularity = 8;
+  std::mutex part_mu;                  // partition state (set_partition vs step entry)
+  std::map<std::vector<uint32_t>, hipStream_t> stream_cache;
+  spd_phase_state phase[2];
+};
+
+namespace spd {
+// host helpers (ctx.cpp)
+int phase_enter(spd_ctx* ctx, int phase, hipStream_t* stream_out);   // adopt pending stream
+int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out);
+int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream);
+int workspace_reserve(spd_ctx* ctx, int phase, size_t bytes, char** out);
+
+// kernel launchers (kernels_*.hip); all enqueue on `stream` and return the launch status
+hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d_tiles, int n_tiles,
+                           const void* k, const void* v, hipStream_t stream);
+hipError_t launch_kv_gather(const PoolGeom& g, const char* pool_base, const TileDesc* d_tiles, int n_tiles,
+                            void* k_out, void* v_out, hipStream_t stream);
+hipError_t launch_decode_gqa(const PoolGeom& g, const char* pool_base, const void* q, void* out,
+                             const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride,
+                             int B, int H, float scale, int chunk_tiles, int max_chunks,
+                             float* ws_o, float* ws_ml, hipStream_t stream);
+hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out, const PrefillWork* d_work,
+                          int n_work, int H, int Hkv, int dqk, int dv, float scale, hipStream_t stream);
+hipError_t launch_probe(int32_t* d_ids, int n_blocks, hipStream_t stream);
+bool prefill_shape_supported(int dqk, int dv);
+int prefill_block_m();
+}  // namespace spd

@@ -1,0 +1,127 @@
+// Page write / gather kernels and the CU-id probe.
+//
+// Paper, "Prefill and Decode Workers": the K, V projections of a request are written into
+// the KV cache during prefill and the cache is updated at every decode iteration.  These
+// kernels move rows between dense [rows, heads, dim] tensors and the library's page layout
+// (internal.h); they are pure copies, bit-exact.
+#include "internal.h"
+
+namespace spd {
+
+typedef unsigned short bf16_t;
+
+// grid (n_tiles, n_kv_heads), block 256.  One workgroup copies the touched token slots of one
+// 16-token tile of one KV head.
+__global__ __launch_bounds__(256) void kv_write_kernel(char* __restrict__ base, uint64_t page_bytes,
+                                                       uint32_t head_bytes, uint32_t tile_bytes,
+                                                       uint32_t tile_k_bytes, const TileDesc* __restrict__ descs,
+                                                       const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+                                                       int Hkv, int dk, int dv) {
+  const TileDesc d = descs[blockIdx.x];
+  const int g = blockIdx.y;
+  char* tile = base + (uint64_t)d.page * page_bytes + (uint64_t)g * head_bytes + (uint64_t)d.sub * tile_bytes;
+  // K part: [chunk][token][8 dims], one 16-byte piece per (chunk, token)
+  const int k_items = (dk >> 3) * TILE_T;
+  for (int i = threadIdx.x; i < k_items; i += blockDim.x) {
+    const int t = i & 15, c = i >> 4;
+    if (t >= d.t_begin && t < d.t_end) {
+      const bf16_t* src = k + ((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dk + c * 8;
+      *(uint4*)(tile + ((size_t)(c * 16 + t) << 4)) = *(const uint4*)src;
+    }
+  }
+  if (v == nullptr) return;
+  // V part: [d/32][token quad][d%16][(d/16)%2][4 tokens], one 16-byte piece per (d/32, quad, d%16)
+  bf16_t* vt = (bf16_t*)(tile + tile_k_bytes);
+  const int v_items = (dv >> 5) * 64;
+  for (int i = threadIdx.x; i < v_items; i += blockDim.x) {
+    const int m = i & 15, c4 = (i >> 4) & 3, blk2 = i >> 6;
+    bf16_t vals[8];
+    bool all = true;
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        const int t = 4 * c4 + tt, dd = 32 * blk2 + 16 * par + m;
+        const bool ok = t >= d.t_begin && t < d.t_end;
+        all = all && ok;
+        vals[par * 4 + tt] = ok ? v[((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dv + dd] : (bf16_t)0;
+      }
+    bf16_t* dst = vt + ((size_t)((blk2 * 4 + c4) * 16 + m) << 3);
+    if (all) {
+      uint4 pk;
+      pk.x = vals[0] | ((uint32_t)vals[1] << 16);
+      pk.y = vals[2] | ((uint32_t)vals[3] << 16);
+      pk.z = vals[4] | ((uint32_t)vals[5] << 16);
+      pk.w = vals[6] | ((uint32_t)vals[7] << 16);
+      *(uint4*)dst = pk;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int t = 4 * c4 + (e & 3);
+        if (t >= d.t_begin && t < d.t_end) dst[e] = vals[e];
+      }
+    }
+  }
+}
+
+// Inverse of kv_write_kernel, element by element through the layout functions.
+__global__ __launch_bounds__(256) void kv_gather_kernel(const char* __restrict__ base, uint64_t page_bytes,
+                                                        uint32_t head_bytes, uint32_t tile_bytes,
+                                                        uint32_t tile_k_bytes, const TileDesc* __restrict__ descs,
+                                                        bf16_t* __restrict__ k_out, bf16_t* __restrict__ v_out,
+                                                        int Hkv, int dk, int dv) {
+  const TileDesc d = descs[blockIdx.x];
+  const int g = blockIdx.y;
+  const char* tile = base + (uint64_t)d.page * page_bytes + (uint64_t)g * head_bytes + (uint64_t)d.sub * tile_bytes;
+  const bf16_t* kt = (const bf16_t*)tile;
+  const bf16_t* vt = (const bf16_t*)(tile + tile_k_bytes);
+  const int nt = d.t_end - d.t_begin;
+  for (int i = threadIdx.x; i < nt * dk; i += blockDim.x) {
+    const int t = d.t_begin + i / dk, dd = i % dk;
+    k_out[((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dk + dd] = kt[k_elem_offset(t, dd)];
+  }
+  if (v_out == nullptr) return;
+  for (int i = threadIdx.x; i < nt * dv; i += blockDim.x) {
+    const int t = d.t_begin + i / dv, dd = i % dv;
+    v_out[((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dv + dd] = vt[v_elem_offset(t, dd)];
+  }
+}
+
+// Each workgroup reports which XCD / shader engine / CU it ran on (hardware id registers).
+__global__ void probe_kernel(int32_t* __restrict__ ids) {
+  if (threadIdx.x == 0) {
+    // s_getreg_b32: simm16 = (size-1) << 11 | offset << 6 | register id
+    const uint32_t hw_id = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_REG_HW_ID
+    const uint32_t xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20);      // HW_REG_XCC_ID, bits 3:0
+    const uint32_t cu = (hw_id >> 8) & 0xf, sh = (hw_id >> 12) & 0x1, se = (hw_id >> 13) & 0x7;
+    ids[blockIdx.x] = (int32_t)((xcc << 16) | (se << 8) | (sh << 4) | cu);
+  }
+  // keep the workgroup resident for a moment so that the launch spreads over the allowed CUs
+  const uint64_t t0 = __builtin_readcyclecounter();
+  while (__builtin_readcyclecounter() - t0 < 20000) {
+  }
+}
+
+hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d_tiles, int n_tiles, const void* k,
+                           const void* v, hipStream_t stream) {
+  if (n_tiles <= 0) return hipSuccess;
+  hipLaunchKernelGGL(kv_write_kernel, dim3(n_tiles, g.Hkv), dim3(256), 0, stream, pool_base, g.page_bytes, g.head_bytes,
+                     g.tile_bytes, g.tile_k_bytes, d_tiles, (const bf16_t*)k, (const bf16_t*)v, g.Hkv, g.dk, g.dv);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_gather(const PoolGeom& g, const char* pool_base, const TileDesc* d_tiles, int n_tiles, void* k_out,
+                            void* v_out, hipStream_t stream) {
+  if (n_tiles <= 0) return hipSuccess;
+  hipLaunchKernelGGL(kv_gather_kernel, dim3(n_tiles, g.Hkv), dim3(256), 0, stream, pool_base, g.page_bytes,
+                     g.head_bytes, g.tile_bytes, g.tile_k_bytes, d_tiles, (bf16_t*)k_out, (bf16_t*)v_out, g.Hkv, g.dk,
+                     g.dv);
+  return hipGetLastError();
+}
+
+hipError_t launch_probe(int32_t* d_ids, int n_blocks, hipStream_t stream) {
+  hipLaunchKernelGGL(probe_kernel, dim3(n_blocks), dim3(64), 0, stream, d_ids);
+  return hipGetLastError();
+}
+
+}  // namespace spd

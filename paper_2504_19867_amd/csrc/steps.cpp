@@ -1,0 +1,249 @@
+// Host side of the two steps and of the page write / gather: validation, atomic block
+// reservation, block-table staging, launch geometry.  All arithmetic of the method runs in
+// the kernels (kernels_*.hip).
+#include "internal.h"
+
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <cmath>
+
+using namespace spd;
+
+namespace spd {
+int64_t blocks_missing_locked(spd_pool* pool, uint64_t req, int64_t n_tokens);
+uint64_t reserve_locked(spd_pool* pool, uint64_t req, int64_t n_tokens);
+}  // namespace spd
+
+static inline size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+// Tile descriptors covering logical positions [start, start + n) of a request whose block
+// table is `bt`; dense row src_row0 maps to position `start`.
+static void build_tile_descs(const PoolGeom& g, const int32_t* bt, int32_t start, int32_t n, int32_t src_row0,
+                             std::vector<TileDesc>& out) {
+  int32_t pos = start, end = start + n;
+  while (pos < end) {
+    int32_t tile = pos / TILE_T, t_begin = pos % TILE_T;
+    int32_t t_end = std::min<int32_t>(TILE_T, t_begin + (end - pos));
+    TileDesc d{};
+    d.src_row = src_row0 + (pos - start);
+    d.page = bt[tile / g.tiles_per_page];
+    d.sub = tile % g.tiles_per_page;
+    d.t_begin = t_begin;
+    d.t_end = t_end;
+    out.push_back(d);
+    pos += t_end - t_begin;
+  }
+}
+
+static int kv_copy(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int32_t start_pos, int32_t n_tokens,
+                   const void* k, const void* v, bool write) {
+  if (!ctx || !pool || pool->ctx != ctx || phase < 0 || phase > 1 || start_pos < 0 || n_tokens <= 0 || !k)
+    return SPD_EINVAL;
+  const PoolGeom& g = pool->geom;
+  if ((g.kind == SPD_KV_GQA) != (v != nullptr)) return SPD_EINVAL;
+  if (ctx->device < 0) return SPD_ESTATE;
+  std::vector<TileDesc> descs;
+  {
+    std::lock_guard<std::mutex> lk(pool->mu);
+    auto it = pool->tables.find(req_id);
+    if (it == pool->tables.end()) return SPD_ENOENT;
+    int64_t need = ((int64_t)start_pos + n_tokens + g.P - 1) / g.P;
+    if ((int64_t)it->second.size() < need) return SPD_EINVAL;
+    build_tile_descs(g, it->second.data(), start_pos, n_tokens, 0, descs);
+  }
+  hipStream_t stream;
+  int rc = phase_enter(ctx, phase, &stream);
+  if (rc != SPD_OK) return rc;
+  size_t bytes = descs.size() * sizeof(TileDesc);
+  spd_stage* st;
+  if ((rc = stage_acquire(ctx, phase, bytes, &st)) != SPD_OK) return rc;
+  memcpy(st->host, descs.data(), bytes);
+  if ((rc = stage_commit(ctx, phase, st, bytes, stream)) != SPD_OK) return rc;
+  if (write)
+    SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)st->dev, (int)descs.size(), k, v, stream));
+  else
+    SPD_HIP(launch_kv_gather(g, pool->base, (const TileDesc*)st->dev, (int)descs.size(), (void*)k, (void*)v, stream));
+  return SPD_OK;
+}
+
+extern "C" int spd_kv_write(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int32_t start_pos,
+                            int32_t n_tokens, const void* k, const void* v) {
+  return kv_copy(ctx, pool, phase, req_id, start_pos, n_tokens, k, v, true);
+}
+
+extern "C" int spd_kv_gather(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int32_t n_tokens,
+                             void* k_out, void* v_out) {
+  return kv_copy(ctx, pool, phase, req_id, 0, n_tokens, k_out, v_out, false);
+}
+
+// ------------------------------------------------------------------------------------------ prefill
+extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_batch* b) {
+  if (!ctx || !pool || pool->ctx != ctx || !b || b->n_req <= 0 || !b->req_ids || !b->cu_seqlens) return SPD_EINVAL;
+  if (!b->q || !b->k || !b->v || !b->out || b->n_q_heads <= 0 || b->n_kv_heads <= 0) return SPD_EINVAL;
+  const PoolGeom& g = pool->geom;
+  if (b->n_q_heads % b->n_kv_heads != 0 || b->cu_seqlens[0] != 0) return SPD_EINVAL;
+  if (!(b->scale > 0.f) || !std::isfinite(b->scale)) return SPD_EINVAL;
+  if (g.kind == SPD_KV_GQA) {
+    if (b->latent || b->n_kv_heads != g.Hkv || b->dim_qk != g.dk || b->dim_v != g.dv) return SPD_EINVAL;
+  } else {
+    if (!b->latent || b->n_kv_heads != b->n_q_heads) return SPD_EINVAL;
+  }
+  if (!prefill_shape_supported(b->dim_qk, b->dim_v)) return SPD_EINVAL;
+  for (int r = 0; r < b->n_req; ++r) {
+    if (b->cu_seqlens[r + 1] <= b->cu_seqlens[r]) return SPD_EINVAL;     // zero-length prompt
+    for (int r2 = 0; r2 < r; ++r2)
+      if (b->req_ids[r2] == b->req_ids[r]) return SPD_EINVAL;
+  }
+  if (ctx->device < 0) return SPD_ESTATE;
+
+  const int BM = prefill_block_m();
+  std::vector<PrefillWork> work;
+  for (int r = 0; r < b->n_req; ++r) {
+    int32_t row0 = b->cu_seqlens[r], len = b->cu_seqlens[r + 1] - row0;
+    for (int32_t t = 0; t < (len + BM - 1) / BM; ++t) work.push_back(PrefillWork{row0, len, t, 0});
+  }
+  // causal work grows with the tile index: heaviest tiles first
+  std::stable_sort(work.begin(), work.end(), [](const PrefillWork& a, const PrefillWork& c) { return a.q_tile > c.q_tile; });
+
+  hipStream_t stream;
+  int rc = phase_enter(ctx, SPD_PHASE_PREFILL, &stream);
+  if (rc != SPD_OK) return rc;
+
+  size_t n_descs = 0;
+  for (int r = 0; r < b->n_req; ++r) n_descs += (size_t)(b->cu_seqlens[r + 1] - b->cu_seqlens[r] + TILE_T - 1) / TILE_T;
+  size_t off_desc = align16(work.size() * sizeof(PrefillWork));
+  size_t bytes = off_desc + n_descs * sizeof(TileDesc);
+  spd_stage* st;
+  if ((rc = stage_acquire(ctx, SPD_PHASE_PREFILL, bytes, &st)) != SPD_OK) return rc;
+  std::vector<TileDesc> descs;
+  descs.reserve(n_descs);
+  {
+    std::lock_guard<std::mutex> lk(pool->mu);                       // atomic: query, get, update
+    int64_t need = 0;
+    for (int r = 0; r < b->n_req; ++r)
+      need += blocks_missing_locked(pool, b->req_ids[r], b->cu_seqlens[r + 1] - b->cu_seqlens[r]);
+    if (need > (int64_t)pool->free_stack.size()) return SPD_ENOMEM;
+    for (int r = 0; r < b->n_req; ++r) {
+      int32_t row0 = b->cu_seqlens[r], len = b->cu_seqlens[r + 1] - row0;
+      reserve_locked(pool, b->req_ids[r], len);
+      build_tile_descs(g, pool->tables[b->req_ids[r]].data(), 0, len, row0, descs);
+    }
+  }
+  memcpy(st->host, work.data(), work.size() * sizeof(PrefillWork));
+  memcpy(st->host + off_desc, descs.data(), descs.size() * sizeof(TileDesc));
+  spd_phase_state& ps = ctx->phase[SPD_PHASE_PREFILL];
+  SPD_HIP(hipEventRecord(ps.ev_start, stream));
+  if ((rc = stage_commit(ctx, SPD_PHASE_PREFILL, st, bytes, stream)) != SPD_OK) return rc;
+  const void* page_src_k = g.kind == SPD_KV_GQA ? b->k : b->latent;
+  const void* page_src_v = g.kind == SPD_KV_GQA ? b->v : nullptr;
+  SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(st->dev + off_desc), (int)descs.size(), page_src_k,
+                          page_src_v, stream));
+  SPD_HIP(launch_prefill(b->q, b->k, b->v, b->out, (const PrefillWork*)st->dev, (int)work.size(), b->n_q_heads,
+                         b->n_kv_heads, b->dim_qk, b->dim_v, b->scale, stream));
+  SPD_HIP(hipEventRecord(ps.ev_end, stream));
+  ps.timed = true;
+  return SPD_OK;
+}
+
+// ------------------------------------------------------------------------------------------ decode
+static int decode_chunk_tiles(int64_t sum_tiles, int Hkv, int cus) {
+  static const char* env = getenv("SPD_DECODE_CHUNK_TILES");
+  if (env && atoi(env) > 0) return (atoi(env) + 7) / 8 * 8;
+  // aim at ~8 workgroups per CU of the decode share so that unequal contexts balance out
+  int64_t target_wgs = (int64_t)cus * 8;
+  int64_t per_head_chunks = std::max<int64_t>(1, target_wgs / std::max(1, Hkv));
+  int64_t c = (sum_tiles + per_head_chunks - 1) / per_head_chunks;
+  c = (c + 7) / 8 * 8;
+  return (int)std::min<int64_t>(std::max<int64_t>(c, 16), 1 << 20);
+}
+
+extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* b) {
+  if (!ctx || !pool || pool->ctx != ctx || !b || b->n_req <= 0 || !b->req_ids || !b->ctx_lens) return SPD_EINVAL;
+  if (!b->q || !b->out || b->n_q_heads <= 0) return SPD_EINVAL;
+  const PoolGeom& g = pool->geom;
+  if (b->n_q_heads % g.Hkv != 0 || b->n_q_heads / g.Hkv > 16) return SPD_EINVAL;
+  if (!(b->scale > 0.f) || !std::isfinite(b->scale)) return SPD_EINVAL;
+  const bool append = b->k_new != nullptr;
+  if (append && (g.kind == SPD_KV_GQA) != (b->v_new != nullptr)) return SPD_EINVAL;
+  if (!append && b->v_new) return SPD_EINVAL;
+  for (int r = 0; r < b->n_req; ++r) {
+    if (b->ctx_lens[r] <= 0) return SPD_EINVAL;                            // empty context
+    if (append)
+      for (int r2 = 0; r2 < r; ++r2)
+        if (b->req_ids[r2] == b->req_ids[r]) return SPD_EINVAL;
+  }
+  if (ctx->device < 0) return SPD_ESTATE;
+  if (g.kind != SPD_KV_GQA) return SPD_ESTATE;   // MLA-latent decode kernel: see kernels_decode_mla.hip
+
+  const int B = b->n_req;
+  int64_t sum_tiles = 0;
+  int32_t max_tiles = 0, max_pages = 0;
+  for (int r = 0; r < B; ++r) {
+    int32_t tiles = (b->ctx_lens[r] + TILE_T - 1) / TILE_T;
+    sum_tiles += tiles;
+    max_tiles = std::max(max_tiles, tiles);
+    max_pages = std::max(max_pages, (b->ctx_lens[r] + g.P - 1) / g.P);
+  }
+  const int bt_stride = max_pages;
+
+  hipStream_t stream;
+  int rc = phase_enter(ctx, SPD_PHASE_DECODE, &stream);
+  if (rc != SPD_OK) return rc;
+  spd_phase_state& ds = ctx->phase[SPD_PHASE_DECODE];
+  const int chunk_tiles = decode_chunk_tiles(sum_tiles, g.Hkv, ds.active_cus);
+  const int max_chunks = (max_tiles + chunk_tiles - 1) / chunk_tiles;
+
+  size_t off_bt = align16(sizeof(int32_t) * (size_t)B);
+  size_t off_desc = align16(off_bt + sizeof(int32_t) * (size_t)B * bt_stride);
+  size_t bytes = off_desc + (append ? sizeof(TileDesc) * (size_t)B : 0);
+  spd_stage* st;
+  if ((rc = stage_acquire(ctx, SPD_PHASE_DECODE, bytes, &st)) != SPD_OK) return rc;
+  char* ws = nullptr;
+  size_t ws_o_bytes = max_chunks > 1 ? sizeof(float) * (size_t)B * b->n_q_heads * max_chunks * g.dv : 0;
+  size_t ws_ml_bytes = max_chunks > 1 ? sizeof(float) * (size_t)B * b->n_q_heads * max_chunks * 2 : 0;
+  if (max_chunks > 1 && (rc = workspace_reserve(ctx, SPD_PHASE_DECODE, ws_o_bytes + ws_ml_bytes, &ws)) != SPD_OK)
+    return rc;
+
+  int32_t* h_ctx = (int32_t*)st->host;
+  int32_t* h_bt = (int32_t*)(st->host + off_bt);
+  TileDesc* h_desc = (TileDesc*)(st->host + off_desc);
+  {
+    std::lock_guard<std::mutex> lk(pool->mu);                       // atomic: query, get, update
+    if (append) {
+      int64_t need = 0;
+      for (int r = 0; r < B; ++r) need += blocks_missing_locked(pool, b->req_ids[r], b->ctx_lens[r]);
+      if (need > (int64_t)pool->free_stack.size()) return SPD_ENOMEM;
+    } else {
+      for (int r = 0; r < B; ++r) {
+        auto it = pool->tables.find(b->req_ids[r]);
+        if (it == pool->tables.end()) return SPD_ENOENT;
+        if ((int64_t)it->second.size() * g.P < b->ctx_lens[r]) return SPD_EINVAL;
+      }
+    }
+    for (int r = 0; r < B; ++r) {
+      if (append) reserve_locked(pool, b->req_ids[r], b->ctx_lens[r]);
+      const std::vector<int32_t>& t = pool->tables[b->req_ids[r]];
+      int32_t pages = (b->ctx_lens[r] + g.P - 1) / g.P;
+      h_ctx[r] = b->ctx_lens[r];
+      memcpy(h_bt + (size_t)r * bt_stride, t.data(), sizeof(int32_t) * pages);
+      for (int32_t p = pages; p < bt_stride; ++p) h_bt[(size_t)r * bt_stride + p] = t[0];
+      if (append) {
+        std::vector<TileDesc> one;
+        build_tile_descs(g, t.data(), b->ctx_lens[r] - 1, 1, r, one);
+        h_desc[r] = one[0];
+      }
+    }
+  }
+  SPD_HIP(hipEventRecord(ds.ev_start, stream));
+  if ((rc = stage_commit(ctx, SPD_PHASE_DECODE, st, bytes, stream)) != SPD_OK) return rc;
+  if (append)
+    SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(st->dev + off_desc), B, b->k_new, b->v_new, stream));
+  SPD_HIP(launch_decode_gqa(g, pool->base, b->q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
+                            bt_stride, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks, (float*)ws,
+                            (float*)(ws ? ws + ws_o_bytes : nullptr), stream));
+  SPD_HIP(hipEventRecord(ds.ev_end, stream));
+  ds.timed = true;
+  return SPD_OK;
+}

@@ -1,0 +1,288 @@
+"""Thin ctypes binding of libsemipd.so: same names as include/semipd.h, argument marshalling only.
+
+Every step of the hot path runs inside the library's HIP kernels.  Device buffers are passed
+as integer addresses (e.g. ``tensor.data_ptr()``); PyTorch is only the caller's way to own
+device memory and is not imported here.  There is no CPU fallback: if the library is missing
+the import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsemipd.so")
+
+SPD_OK, SPD_EINVAL, SPD_ENOMEM, SPD_ENOENT, SPD_EHIP, SPD_ESTATE = 0, -1, -2, -3, -5, -6
+SPD_PHASE_PREFILL, SPD_PHASE_DECODE = 0, 1
+SPD_KV_GQA, SPD_KV_MLA_LATENT = 0, 1
+
+EXPORTS = [
+    "spd_ctx_create", "spd_ctx_destroy", "spd_device_info", "spd_pool_bytes", "spd_pool_create",
+    "spd_pool_destroy", "spd_pool_stats", "spd_kv_reserve", "spd_kv_free", "spd_kv_block_table",
+    "spd_kv_free_list", "spd_kv_write", "spd_kv_gather", "spd_prefill_step", "spd_decode_step",
+    "spd_phase_sync", "spd_phase_query", "spd_phase_wait_for", "spd_phase_stream", "spd_phase_last_ms",
+    "spd_set_partition", "spd_get_partition", "spd_phase_cu_mask", "spd_partition_masks",
+    "spd_phase_probe_cus", "spd_strerror", "spd_last_hip_error",
+]
+
+
+class SpdError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {strerror(status)} (status {status}, hip error {last_hip_error()})")
+
+
+class PoolExhausted(SpdError):
+    pass
+
+
+class spd_pool_desc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("page_tokens", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("dim_k", C.c_int32), ("dim_v", C.c_int32), ("num_pages", C.c_int64)]
+
+
+class spd_prefill_batch(C.Structure):
+    _fields_ = [("n_req", C.c_int32), ("req_ids", C.POINTER(C.c_uint64)), ("cu_seqlens", C.POINTER(C.c_int32)),
+                ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p), ("latent", C.c_void_p),
+                ("out", C.c_void_p), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("dim_qk", C.c_int32), ("dim_v", C.c_int32), ("scale", C.c_float)]
+
+
+class spd_decode_batch(C.Structure):
+    _fields_ = [("n_req", C.c_int32), ("req_ids", C.POINTER(C.c_uint64)), ("ctx_lens", C.POINTER(C.c_int32)),
+                ("q", C.c_void_p), ("k_new", C.c_void_p), ("v_new", C.c_void_p), ("out", C.c_void_p),
+                ("n_q_heads", C.c_int32), ("scale", C.c_float)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
+    P = C.POINTER
+    sig = {
+        "spd_ctx_create": [C.c_int, P(vp)],
+        "spd_ctx_destroy": [vp],
+        "spd_device_info": [vp, P(C.c_int), P(C.c_int), P(C.c_int)],
+        "spd_pool_bytes": [P(spd_pool_desc), P(u64)],
+        "spd_pool_create": [vp, vp, u64, P(spd_pool_desc), P(vp)],
+        "spd_pool_destroy": [vp],
+        "spd_pool_stats": [vp, P(i64), P(i64), P(i64), P(u64)],
+        "spd_kv_reserve": [vp, u64, i32, P(u64)],
+        "spd_kv_free": [vp, u64, P(u64)],
+        "spd_kv_block_table": [vp, u64, P(i32), i32, P(i32)],
+        "spd_kv_free_list": [vp, P(i32), i64, P(i64)],
+        "spd_kv_write": [vp, vp, C.c_int, u64, i32, i32, vp, vp],
+        "spd_kv_gather": [vp, vp, C.c_int, u64, i32, vp, vp],
+        "spd_prefill_step": [vp, vp, P(spd_prefill_batch)],
+        "spd_decode_step": [vp, vp, P(spd_decode_batch)],
+        "spd_phase_sync": [vp, C.c_int],
+        "spd_phase_query": [vp, C.c_int, P(C.c_int)],
+        "spd_phase_wait_for": [vp, C.c_int, C.c_int],
+        "spd_phase_stream": [vp, C.c_int, P(vp)],
+        "spd_phase_last_ms": [vp, C.c_int, P(C.c_float)],
+        "spd_set_partition": [vp, C.c_int, C.c_int],
+        "spd_get_partition": [vp, P(C.c_int), P(C.c_int), P(C.c_int), P(C.c_int)],
+        "spd_phase_cu_mask": [vp, C.c_int, P(C.c_uint32), i32, P(i32)],
+        "spd_partition_masks": [C.c_int, C.c_int, C.c_int, C.c_int, P(C.c_uint32), P(C.c_uint32), P(C.c_int), P(C.c_int)],
+        "spd_phase_probe_cus": [vp, C.c_int, i32, P(i32), i32, P(i32)],
+        "spd_last_hip_error": [],
+    }
+    for name, args in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = C.c_int
+    lib.spd_strerror.argtypes = [C.c_int]
+    lib.spd_strerror.restype = C.c_char_p
+    return lib
+
+
+lib = _load()
+
+
+def strerror(status: int) -> str:
+    return lib.spd_strerror(status).decode()
+
+
+def last_hip_error() -> int:
+    return lib.spd_last_hip_error()
+
+
+def _check(status: int, what: str) -> None:
+    if status == SPD_ENOMEM:
+        raise PoolExhausted(status, what)
+    if status != SPD_OK:
+        raise SpdError(status, what)
+
+
+def _ptr(x) -> Optional[int]:
+    """Device address of a tensor-like (has data_ptr()), an int address, or None."""
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return int(x)
+
+
+# ----------------------------------------------------------------------------- thin object wrappers
+class Context:
+    """spd_ctx: device=-1 makes a host-only context (allocator and partition state only)."""
+
+    def __init__(self, device: int = 0):
+        h = C.c_void_p()
+        _check(lib.spd_ctx_create(device, C.byref(h)), "spd_ctx_create")
+        self.h = h
+        self.device = device
+
+    def close(self) -> None:
+        if self.h:
+            _check(lib.spd_ctx_destroy(self.h), "spd_ctx_destroy")
+            self.h = None
+
+    def device_info(self) -> Tuple[int, int, int]:
+        a, b, c = C.c_int(), C.c_int(), C.c_int()
+        _check(lib.spd_device_info(self.h, C.byref(a), C.byref(b), C.byref(c)), "spd_device_info")
+        return a.value, b.value, c.value
+
+    def set_partition(self, prefill_cus: int, decode_cus: int) -> None:
+        _check(lib.spd_set_partition(self.h, prefill_cus, decode_cus), "spd_set_partition")
+
+    def get_partition(self) -> Tuple[int, int, int, int]:
+        v = [C.c_int() for _ in range(4)]
+        _check(lib.spd_get_partition(self.h, *[C.byref(x) for x in v]), "spd_get_partition")
+        return tuple(x.value for x in v)
+
+    def phase_cu_mask(self, phase: int) -> List[int]:
+        words = (C.c_uint32 * 32)()
+        n = C.c_int32()
+        _check(lib.spd_phase_cu_mask(self.h, phase, words, 32, C.byref(n)), "spd_phase_cu_mask")
+        return [int(words[i]) for i in range(n.value)]
+
+    def phase_sync(self, phase: int) -> None:
+        _check(lib.spd_phase_sync(self.h, phase), "spd_phase_sync")
+
+    def phase_query(self, phase: int) -> bool:
+        d = C.c_int()
+        _check(lib.spd_phase_query(self.h, phase, C.byref(d)), "spd_phase_query")
+        return bool(d.value)
+
+    def phase_wait_for(self, phase: int, other: int) -> None:
+        _check(lib.spd_phase_wait_for(self.h, phase, other), "spd_phase_wait_for")
+
+    def phase_stream(self, phase: int) -> int:
+        s = C.c_void_p()
+        _check(lib.spd_phase_stream(self.h, phase, C.byref(s)), "spd_phase_stream")
+        return s.value or 0
+
+    def phase_last_ms(self, phase: int) -> float:
+        ms = C.c_float()
+        _check(lib.spd_phase_last_ms(self.h, phase, C.byref(ms)), "spd_phase_last_ms")
+        return ms.value
+
+    def phase_probe_cus(self, phase: int, n_blocks: int = 4096) -> List[int]:
+        ids = (C.c_int32 * 2048)()
+        n = C.c_int32()
+        _check(lib.spd_phase_probe_cus(self.h, phase, n_blocks, ids, 2048, C.byref(n)), "spd_phase_probe_cus")
+        return [int(ids[i]) for i in range(n.value)]
+
+
+def partition_masks(total_cus: int, granularity: int, prefill_cus: int, decode_cus: int):
+    words = (total_cus + 31) // 32
+    pm, dm = (C.c_uint32 * words)(), (C.c_uint32 * words)()
+    p, d = C.c_int(), C.c_int()
+    _check(lib.spd_partition_masks(total_cus, granularity, prefill_cus, decode_cus, pm, dm, C.byref(p), C.byref(d)),
+           "spd_partition_masks")
+    return list(pm), list(dm), p.value, d.value
+
+
+def pool_bytes(kind: int, page_tokens: int, n_kv_heads: int, dim_k: int, dim_v: int, num_pages: int) -> int:
+    desc = spd_pool_desc(kind, page_tokens, n_kv_heads, dim_k, dim_v, num_pages)
+    out = C.c_uint64()
+    _check(lib.spd_pool_bytes(C.byref(desc), C.byref(out)), "spd_pool_bytes")
+    return out.value
+
+
+class Pool:
+    """spd_pool over caller-owned device memory (`dev_mem`: tensor or address; None with a host-only ctx)."""
+
+    def __init__(self, ctx: Context, dev_mem, nbytes: int, kind: int, page_tokens: int, n_kv_heads: int,
+                 dim_k: int, dim_v: int, num_pages: int):
+        self.ctx = ctx
+        self.desc = spd_pool_desc(kind, page_tokens, n_kv_heads, dim_k, dim_v, num_pages)
+        self._mem = dev_mem                       # keep the tensor alive
+        h = C.c_void_p()
+        _check(lib.spd_pool_create(ctx.h, _ptr(dev_mem), nbytes, C.byref(self.desc), C.byref(h)), "spd_pool_create")
+        self.h = h
+
+    def close(self) -> None:
+        if self.h:
+            _check(lib.spd_pool_destroy(self.h), "spd_pool_destroy")
+            self.h = None
+
+    def stats(self) -> Tuple[int, int, int, int]:
+        t, f, l, s = C.c_int64(), C.c_int64(), C.c_int64(), C.c_uint64()
+        _check(lib.spd_pool_stats(self.h, C.byref(t), C.byref(f), C.byref(l), C.byref(s)), "spd_pool_stats")
+        return t.value, f.value, l.value, s.value
+
+    def kv_reserve(self, req_id: int, n_tokens_total: int) -> int:
+        seq = C.c_uint64()
+        _check(lib.spd_kv_reserve(self.h, req_id, n_tokens_total, C.byref(seq)), "spd_kv_reserve")
+        return seq.value
+
+    def kv_free(self, req_id: int) -> int:
+        seq = C.c_uint64()
+        _check(lib.spd_kv_free(self.h, req_id, C.byref(seq)), "spd_kv_free")
+        return seq.value
+
+    def kv_block_table(self, req_id: int) -> List[int]:
+        n = C.c_int32()
+        st = lib.spd_kv_block_table(self.h, req_id, None, 0, C.byref(n))
+        if st not in (SPD_OK, SPD_EINVAL):
+            _check(st, "spd_kv_block_table")
+        buf = (C.c_int32 * max(1, n.value))()
+        _check(lib.spd_kv_block_table(self.h, req_id, buf, n.value, C.byref(n)), "spd_kv_block_table")
+        return [int(buf[i]) for i in range(n.value)]
+
+    def kv_free_list(self) -> List[int]:
+        import numpy as np
+        total = self.stats()[0]
+        buf = np.empty(total, dtype=np.int32)
+        n = C.c_int64()
+        _check(lib.spd_kv_free_list(self.h, buf.ctypes.data_as(C.POINTER(C.c_int32)), total, C.byref(n)),
+               "spd_kv_free_list")
+        return buf[: n.value].tolist()
+
+    def kv_write(self, phase: int, req_id: int, start_pos: int, n_tokens: int, k, v=None) -> None:
+        _check(lib.spd_kv_write(self.ctx.h, self.h, phase, req_id, start_pos, n_tokens, _ptr(k), _ptr(v)),
+               "spd_kv_write")
+
+    def kv_gather(self, phase: int, req_id: int, n_tokens: int, k_out, v_out=None) -> None:
+        _check(lib.spd_kv_gather(self.ctx.h, self.h, phase, req_id, n_tokens, _ptr(k_out), _ptr(v_out)),
+               "spd_kv_gather")
+
+    def prefill_step(self, req_ids: Sequence[int], cu_seqlens: Sequence[int], q, k, v, out, n_q_heads: int,
+                     n_kv_heads: int, dim_qk: int, dim_v: int, scale: float, latent=None) -> None:
+        n = len(req_ids)
+        ids = (C.c_uint64 * n)(*req_ids)
+        cu = (C.c_int32 * (n + 1))(*[int(x) for x in cu_seqlens])
+        b = spd_prefill_batch(n, ids, cu, _ptr(q), _ptr(k), _ptr(v), _ptr(latent), _ptr(out), n_q_heads,
+                              n_kv_heads, dim_qk, dim_v, scale)
+        _check(lib.spd_prefill_step(self.ctx.h, self.h, C.byref(b)), "spd_prefill_step")
+
+    def make_decode_batch(self, req_ids: Sequence[int], ctx_lens: Sequence[int], q, out, n_q_heads: int,
+                          scale: float, k_new=None, v_new=None):
+        """Marshal once; the returned object can be passed to decode_step_batch repeatedly."""
+        n = len(req_ids)
+        ids = (C.c_uint64 * n)(*req_ids)
+        lens = (C.c_int32 * n)(*[int(x) for x in ctx_lens])
+        b = spd_decode_batch(n, ids, lens, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), n_q_heads, scale)
+        b._keep = (ids, lens, q, out, k_new, v_new)
+        return b
+
+    def decode_step_batch(self, batch) -> None:
+        _check(lib.spd_decode_step(self.ctx.h, self.h, C.byref(batch)), "spd_decode_step")
+
+    def decode_step(self, req_ids, ctx_lens, q, out, n_q_heads: int, scale: float, k_new=None, v_new=None) -> None:
+        self.decode_step_batch(self.make_decode_batch(req_ids, ctx_lens, q, out, n_q_heads, scale, k_new, v_new))

@@ -1,0 +1,244 @@
+"""Host logic of libsemipd through the C ABI, no GPU: exports, allocator == oracle bit for bit,
+the two-worker atomicity scenario, partition masks, error behaviour."""
+import os
+import re
+import threading
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle.allocator import BlockAllocator, PoolExhausted
+from paper_2504_19867_amd import semipd as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+
+
+def host_pool(num_pages=64, P=16, kind=S.SPD_KV_GQA, hkv=2, dk=64, dv=64):
+    ctx = S.Context(-1)
+    return ctx, S.Pool(ctx, None, 0, kind, P, hkv, dk, dv, num_pages)
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "semipd.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(spd_[a-z_0-9]+)\s*\(", header))
+    assert declared, "no declarations found"
+    assert declared == set(S.EXPORTS)
+    for name in declared:
+        assert hasattr(S.lib, name), f"{name} declared in semipd.h but not exported"
+
+
+def test_policy_trace_matches_golden_fixture():
+    ctx, pool = host_pool(8, 4 * 4)        # the fixture uses 4 tokens / page; the library needs P % 16 == 0
+    scale = 4                              # so token counts are multiplied by 4 (same page counts)
+    for line in open(os.path.join(GOLDEN, "allocator_policy_trace.txt")):
+        if not line.strip() or line[0] == "#":
+            continue
+        op, want, nfree = (p.strip() for p in line.split("|"))
+        name, req, n = op.split()
+        req, n = int(req), int(n)
+        before = (pool.kv_free_list(), pool.stats())
+        if want == "ENOMEM":
+            with pytest.raises(S.PoolExhausted):
+                pool.kv_reserve(req, (n - 1) * scale + 1)
+            assert (pool.kv_free_list(), pool.stats()) == before
+        elif want == "ENOENT":
+            with pytest.raises(S.SpdError) as e:
+                pool.kv_free(req)
+            assert e.value.status == S.SPD_ENOENT
+            assert (pool.kv_free_list(), pool.stats()) == before
+        elif name == "reserve":
+            pool.kv_reserve(req, (n - 1) * scale + 1)      # same ceil(n / 4) pages
+            assert pool.kv_block_table(req) == [int(x) for x in want.split()]
+        else:
+            pool.kv_free(req)
+        assert pool.stats()[1] == int(nfree)
+
+
+def test_random_churn_is_bit_exact_with_oracle():
+    rng = np.random.default_rng(1)
+    ctx, pool = host_pool(97, 16)
+    ora = BlockAllocator(97, 16)
+    live = {}
+    for step in range(3000):
+        r = int(rng.integers(0, 30))
+        if r in live and rng.random() < 0.3:
+            assert pool.kv_free(r) == ora.free(r)
+            del live[r]
+        else:
+            n = live.get(r, 0) + int(rng.integers(1, 90))
+            try:
+                want = ora.reserve(r, n)
+            except PoolExhausted:
+                with pytest.raises(S.PoolExhausted):
+                    pool.kv_reserve(r, n)
+                continue
+            assert pool.kv_reserve(r, n) == want
+            live[r] = n
+        if step % 100 == 0:
+            assert pool.kv_free_list() == ora.free_stack
+            for r2 in live:
+                assert pool.kv_block_table(r2) == ora.block_table(r2)
+            total, free, nlive, seq = pool.stats()
+            assert (total, free, nlive, seq) == (97, ora.n_free, len(ora.tables), ora.op_seq)
+    assert pool.kv_free_list() == ora.free_stack
+
+
+def test_two_workers_allocate_atomically_and_replay_matches_oracle():
+    """The paper's write-after-read hazard: two asynchronous workers query / get / update at once.
+    Each call's sequence number gives the linearised order; the oracle replays it and must land
+    in exactly the same tables and free list, and no block may ever be owned twice."""
+    ctx, pool = host_pool(512, 16)
+    logs = [[], []]
+
+    def worker(wid):
+        rng = np.random.default_rng(100 + wid)
+        mine = {}
+        for _ in range(4000):
+            r = wid * 1000 + int(rng.integers(0, 20))
+            if r in mine and rng.random() < 0.4:
+                logs[wid].append((pool.kv_free(r), "free", r, 0))
+                del mine[r]
+            else:
+                n = mine.get(r, 0) + int(rng.integers(1, 200))
+                try:
+                    logs[wid].append((pool.kv_reserve(r, n), "reserve", r, n))
+                    mine[r] = n
+                except S.PoolExhausted:
+                    pass
+
+    ts = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    ops = sorted(logs[0] + logs[1])
+    seqs = [o[0] for o in ops]
+    assert seqs == list(range(1, len(ops) + 1)), "sequence numbers are not a gap-free linear order"
+    ora = BlockAllocator(512, 16)
+    for _, op, r, n in ops:
+        ora.reserve(r, n) if op == "reserve" else ora.free(r)
+    assert pool.kv_free_list() == ora.free_stack
+    owned = []
+    for r in ora.tables:
+        t = pool.kv_block_table(r)
+        assert t == ora.block_table(r)
+        owned += t
+    assert len(owned) == len(set(owned))
+    assert pool.stats() == (512, ora.n_free, len(ora.tables), ora.op_seq)
+
+
+def test_scramble_ops_same_on_both_sides():
+    ctx, pool = host_pool(256, 16)
+    ora = BlockAllocator(256, 16)
+    for op, r, n in W.scramble_ops(200, 16, seed=3):
+        if op == "reserve":
+            pool.kv_reserve(r, n), ora.reserve(r, n)
+        else:
+            pool.kv_free(r), ora.free(r)
+    assert pool.kv_free_list() == ora.free_stack
+    pool.kv_reserve(1, 16 * 50)
+    ora.reserve(1, 16 * 50)
+    assert pool.kv_block_table(1) == ora.block_table(1) != list(range(50))
+
+
+def test_allocator_argument_errors_change_nothing():
+    ctx, pool = host_pool(4, 16)
+    pool.kv_reserve(1, 20)
+    snap = (pool.kv_free_list(), pool.stats(), pool.kv_block_table(1))
+    for bad in (0, -5):
+        with pytest.raises(S.SpdError) as e:
+            pool.kv_reserve(2, bad)
+        assert e.value.status == S.SPD_EINVAL
+    with pytest.raises(S.PoolExhausted):
+        pool.kv_reserve(1, 16 * 5)
+    with pytest.raises(S.SpdError) as e:
+        pool.kv_block_table(99)
+    assert e.value.status == S.SPD_ENOENT
+    assert (pool.kv_free_list(), pool.stats(), pool.kv_block_table(1)) == snap
+
+
+def test_pool_geometry_and_validation():
+    c2 = W.get_config("c2").layer
+    assert S.pool_bytes(S.SPD_KV_GQA, 16, c2.n_kv_heads, 128, 128, 10) == 10 * c2.page_bytes
+    c4 = W.get_config("c4").layer
+    assert S.pool_bytes(S.SPD_KV_MLA_LATENT, 64, 1, 576, 512, 3) == 3 * c4.page_bytes
+    for bad in ((S.SPD_KV_GQA, 15, 8, 128, 128, 4), (S.SPD_KV_GQA, 16, 8, 96, 96, 4), (S.SPD_KV_GQA, 16, 8, 128, 64, 4),
+                (S.SPD_KV_GQA, 16, 8, 128, 128, 0), (S.SPD_KV_MLA_LATENT, 64, 2, 576, 512, 4), (7, 16, 8, 128, 128, 4)):
+        with pytest.raises(S.SpdError) as e:
+            S.pool_bytes(*bad)
+        assert e.value.status == S.SPD_EINVAL
+
+
+def bits(words):
+    return {32 * i + b for i, w in enumerate(words) for b in range(32) if (w >> b) & 1}
+
+
+@pytest.mark.parametrize("p,d", [(77, 179), (128, 128), (102, 154), (179, 77), (8, 248), (1, 1)])
+def test_partition_masks_disjoint_and_balanced(p, d):
+    pm, dm, pr, dr = S.partition_masks(256, 8, p, d)
+    pb, db = bits(pm), bits(dm)
+    assert len(pb) == pr and len(db) == dr and pr % 8 == 0 and dr % 8 == 0
+    assert abs(pr - p) <= 7 and abs(dr - d) <= 7
+    assert not (pb & db), "partitions overlap although the counts fit"
+    assert pb == set(range(pr)) and db == set(range(256 - dr, 256))
+    # consecutive mask bits walk the XCDs, so each XCD contributes equally to each share
+    for s in (pb, db):
+        per_xcd = [sum(1 for b in s if b % 8 == x) for x in range(8)]
+        assert len(set(per_xcd)) == 1
+
+
+def test_partition_masks_oversubscription_overlaps():
+    pm, dm, pr, dr = S.partition_masks(256, 8, 256, 256)      # the paper's (100, 100) setting
+    assert pr == dr == 256 and bits(pm) == bits(dm) == set(range(256))
+    pm, dm, pr, dr = S.partition_masks(256, 8, 160, 160)
+    assert len(bits(pm) & bits(dm)) == 64
+    for bad in ((0, 8), (8, 0), (-1, 5)):
+        with pytest.raises(S.SpdError):
+            S.partition_masks(256, 8, *bad)
+    with pytest.raises(S.SpdError):
+        S.partition_masks(250, 8, 10, 10)
+
+
+def test_host_only_context_stages_partition_and_refuses_gpu_work():
+    ctx, pool = host_pool(16, 16)
+    assert ctx.device_info() == (256, 8, 8)
+    assert ctx.get_partition() == (256, 256, 256, 256)
+    ctx.set_partition(102, 154)
+    # delayed switching: staged, not adopted until the phase's next step
+    assert ctx.get_partition() == (256, 256, 104, 152)
+    assert bits(ctx.phase_cu_mask(S.SPD_PHASE_PREFILL)) == set(range(256))
+    pool.kv_reserve(1, 16)
+    for fn in (lambda: ctx.phase_sync(0), lambda: ctx.phase_stream(1), lambda: pool.kv_write(0, 1, 0, 4, 4096, 4096),
+               lambda: pool.decode_step([1], [4], 4096, 4096, 2, 1.0),
+               lambda: pool.prefill_step([2], [0, 8], 4096, 4096, 4096, 4096, 2, 2, 64, 64, 1.0)):
+        with pytest.raises(S.SpdError) as e:
+            fn()
+        assert e.value.status == S.SPD_ESTATE
+    assert pool.stats()[2] == 1          # the refused prefill reserved nothing
+
+
+def test_step_argument_validation():
+    ctx, pool = host_pool(16, 16)
+    pool.kv_reserve(1, 16)
+    cases = [
+        lambda: pool.decode_step([1], [0], 4096, 4096, 2, 1.0),                    # empty context
+        lambda: pool.decode_step([1], [4], 4096, 4096, 3, 1.0),                    # heads not a multiple of KV heads
+        lambda: pool.decode_step([1], [4], 4096, 4096, 64, 1.0),                   # > 16 query heads per KV head
+        lambda: pool.decode_step([1], [4], None, 4096, 2, 1.0),
+        lambda: pool.prefill_step([2], [0, 0], 4096, 4096, 4096, 4096, 2, 2, 64, 64, 1.0),   # zero-length prompt
+        lambda: pool.prefill_step([2, 2], [0, 4, 8], 4096, 4096, 4096, 4096, 2, 2, 64, 64, 1.0),  # duplicate id
+        lambda: pool.prefill_step([2], [0, 8], 4096, 4096, 4096, 4096, 2, 2, 128, 128, 1.0),  # dims differ from pool
+        lambda: pool.prefill_step([2], [0, 8], 4096, 4096, 4096, 4096, 2, 2, 64, 64, 1.0, latent=4096),
+        lambda: pool.decode_step([1], [4], 4096, 4096, 2, 0.0),                    # scale must be > 0
+        lambda: pool.prefill_step([2], [0, 8], 4096, 4096, 4096, 4096, 2, 2, 64, 64, -1.0),
+        lambda: pool.kv_write(0, 1, 0, 0, 4096, 4096),
+        lambda: pool.kv_write(0, 1, 0, 4, 4096, None),
+    ]
+    for fn in cases:
+        with pytest.raises(S.SpdError) as e:
+            fn()
+        assert e.value.status == S.SPD_EINVAL
+    assert pool.stats()[2] == 1
