@@ -1,0 +1,271 @@
+"""bench.py - throughput of the semi-PD hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: one prefill step
+(block reservation, K/V page write, causal attention over the prompt batch) on the prefill CU
+partition, running concurrently with `decode_per_prefill` decode steps (paged attention of the
+decode batch over the unified pool) on the decode CU partition; the ratio is calibrated in the
+warm-up so that both partitions stay busy, as the paper's two asynchronous workers do.
+Workload: benchmark configs[1] (Llama-3-8B attention layer shape).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PRE, DEC = 0, 1
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c2")
+    ap.add_argument("--split", default="50/50", help="prefill%%/decode%% of the CUs for the headline run")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the CU-split sweep (solo + concurrent per split)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--pool-gb", type=float, default=None, help="override pool size (GB)")
+    ap.add_argument("--only", default=None, choices=[None, "prefill", "decode"],
+                    help="profiling aid: run only one phase in the timed region")
+    return ap.parse_args()
+
+
+def median(xs):
+    s = sorted(xs)
+    return s[len(s) // 2] if s else float("nan")
+
+
+class Bench:
+    def __init__(self, cfg, pool_gb=None):
+        import torch
+        from paper_2504_19867_amd import semipd as S
+        self.torch, self.S, self.cfg = torch, S, cfg
+        L = cfg.layer
+        self.L = L
+        self.dev = torch.device("cuda:0")
+        self.ctx = S.Context(0)
+        self.total_cus, self.xcds, self.gran = self.ctx.device_info()
+        num_pages = cfg.num_pages if pool_gb is None else int(pool_gb * 1e9) // L.page_bytes
+        self.num_pages = num_pages
+        nbytes = S.pool_bytes(S.SPD_KV_GQA, L.page_tokens, L.n_kv_heads, L.dim_qk, L.dim_v, num_pages)
+        self.mem = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
+        self.pool = S.Pool(self.ctx, self.mem, nbytes, S.SPD_KV_GQA, L.page_tokens, L.n_kv_heads, L.dim_qk, L.dim_v,
+                           num_pages)
+        self.scale = 1.0 / math.sqrt(L.dim_qk)
+        gen = torch.Generator(device=self.dev)
+        gen.manual_seed(cfg.seed)
+
+        def randn(*shape):
+            return torch.randn(*shape, generator=gen, device=self.dev, dtype=torch.float32).to(torch.bfloat16)
+
+        # scattered physical pages, as after long serving
+        import workloads as W
+        touched = min(num_pages - 8, 4 * sum(-(-n // L.page_tokens) for n in cfg.decode_ctx) * 3)
+        for op, r, n in W.scramble_ops(touched, L.page_tokens, cfg.seed):
+            self.pool.kv_reserve(r, n) if op == "reserve" else self.pool.kv_free(r)
+
+        # decode: 3 disjoint request sets (> 256 MB apart in use) so that no step finds its KV in cache
+        self.B = len(cfg.decode_ctx)
+        self.n_sets = 3
+        self.dec_batches = []
+        for s in range(self.n_sets):
+            ids = [10_000 * (s + 1) + i for i in range(self.B)]
+            for rid, n in zip(ids, cfg.decode_ctx):
+                self.pool.kv_reserve(rid, n)
+                k = randn(n, L.n_kv_heads, L.dim_qk)
+                v = randn(n, L.n_kv_heads, L.dim_v)
+                self.pool.kv_write(DEC, rid, 0, n, k, v)
+            self.ctx.phase_sync(DEC)
+            q = randn(self.B, L.n_q_heads, L.dim_qk)
+            out = torch.empty((self.B, L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=self.dev)
+            self.dec_batches.append(self.pool.make_decode_batch(ids, cfg.decode_ctx, q, out, L.n_q_heads, self.scale))
+        # prefill: 2 input sets
+        self.T = sum(cfg.prefill_lens)
+        cu = [0]
+        for n in cfg.prefill_lens:
+            cu.append(cu[-1] + n)
+        self.pre_batches = []
+        for s in range(2):
+            q = randn(self.T, L.n_q_heads, L.dim_qk)
+            k = randn(self.T, L.n_kv_heads, L.dim_qk)
+            v = randn(self.T, L.n_kv_heads, L.dim_v)
+            out = torch.empty((self.T, L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=self.dev)
+            ids = [100 * (s + 1) + i for i in range(len(cfg.prefill_lens))]
+            self.pre_batches.append(self.pool.make_prefill_batch(ids, cu, q, k, v, out, L.n_q_heads, L.n_kv_heads,
+                                                                 L.dim_qk, L.dim_v, self.scale))
+        torch.cuda.synchronize()
+        # algorithmic work
+        G = L.n_q_heads
+        self.prefill_flops = sum(2.0 * (L.dim_qk + L.dim_v) * G * n * (n + 1) / 2 for n in cfg.prefill_lens)
+        kv_bytes = sum(cfg.decode_ctx) * L.n_kv_heads * (L.dim_qk + L.dim_v) * 2
+        qo_bytes = self.B * L.n_q_heads * (L.dim_qk + L.dim_v) * 2
+        self.decode_bytes = float(kv_bytes + qo_bytes)
+        self.n_pre = self.n_dec = 0
+
+    def prefill(self):
+        self.pool.prefill_step_batch(self.pre_batches[self.n_pre % 2])
+        self.n_pre += 1
+
+    def decode(self):
+        self.pool.decode_step_batch(self.dec_batches[self.n_dec % self.n_sets])
+        self.n_dec += 1
+
+    def sync(self):
+        self.ctx.phase_sync(PRE)
+        self.ctx.phase_sync(DEC)
+
+    def set_split(self, p_pct, d_pct):
+        self.ctx.set_partition(max(1, round(self.total_cus * p_pct / 100)), max(1, round(self.total_cus * d_pct / 100)))
+        self.prefill(); self.decode(); self.sync()          # both phases adopt the new streams
+        return self.ctx.get_partition()[:2]
+
+    def time_solo(self, phase, n):
+        """median kernel-level and step-level ms of `n` back-to-back steps of one phase, other phase idle"""
+        fn = self.prefill if phase == PRE else self.decode
+        for _ in range(3):
+            fn()
+        self.ctx.phase_sync(phase)
+        self.ctx.phase_kernel_ms(phase)
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        self.ctx.phase_sync(phase)
+        wall = (time.perf_counter() - t0) * 1e3 / n
+        return median(self.ctx.phase_kernel_ms(phase)), wall
+
+    def run_concurrent(self, steps, r, only=None):
+        """`steps` steps of (1 prefill || r decodes); returns wall ms/step and per-phase kernel ms lists"""
+        torch = self.torch
+        self.sync()
+        self.ctx.phase_kernel_ms(PRE); self.ctx.phase_kernel_ms(DEC)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            if only != "decode":
+                self.prefill()
+            if only != "prefill":
+                for _ in range(r):
+                    self.decode()
+        self.sync()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        return wall_ms, self.ctx.phase_kernel_ms(PRE), self.ctx.phase_kernel_ms(DEC)
+
+
+def cpu_baseline(cfg, r):
+    """The fp64 oracle, as it stands, timed on this host on a bounded sample of the same workload."""
+    import numpy as np
+    import workloads as W
+    from oracle import attention as OA
+    L = cfg.layer
+    scale = 1.0 / math.sqrt(L.dim_qk)
+    G = L.n_q_heads // L.n_kv_heads
+    # prefill sample: request 0, all heads
+    n0 = cfg.prefill_lens[0]
+    q, k, v, cu = W.prefill_inputs(L, (n0,), cfg.seed)
+    f = lambda b: W.bf16_bits_to_f32(b).astype(np.float64)
+    t0 = time.perf_counter()
+    OA.prefill_attention(f(q), f(k), f(v), cu, scale)
+    t_p = (time.perf_counter() - t0) * (sum(cfg.prefill_lens) / n0)                   # whole prefill batch
+    # decode sample: first half of the requests, all heads
+    ns = cfg.decode_ctx[: max(1, len(cfg.decode_ctx) // 2)]
+    qd, ks, vs = W.decode_inputs(L, ns, cfg.seed + 1)
+    t0 = time.perf_counter()
+    for i in range(len(ns)):
+        OA.decode_attention(f(qd[i]), f(ks[i]), f(vs[i]), scale)
+    t_d = (time.perf_counter() - t0) * (sum(cfg.decode_ctx) / sum(ns))                # whole decode batch
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    tokens = sum(cfg.prefill_lens) + r * len(cfg.decode_ctx)
+    return {"value": tokens / (t_p + r * t_d), "unit": "tokens/s (one attention layer)", "cores": int(cores),
+            "kind": "oracle",
+            "sample": f"prefill: request 0 of {len(cfg.prefill_lens)}, all heads ({n0} tokens), scaled by tokens; "
+                      f"decode: first {len(ns)} of {len(cfg.decode_ctx)} requests, all heads, scaled by context tokens; same "
+                      f"1 prefill : {r} decode step mix as the GPU run",
+            "prefill_tok_s": sum(cfg.prefill_lens) / t_p, "decode_tok_s": len(cfg.decode_ctx) / t_d}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the hot path of one MI355X; --gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import workloads as W
+    cfg = W.get_config(args.config)
+    bench = Bench(cfg, args.pool_gb)
+    bench.ctx.set_kernel_timing(True)
+    p_pct, d_pct = (int(x) for x in args.split.split("/"))
+
+    def measure_split(pp, dp, steps, warmup, only=None):
+        p_cus, d_cus = bench.set_split(pp, dp)
+        solo_p_k, solo_p_w = bench.time_solo(PRE, max(5, steps // 4))
+        solo_d_k, solo_d_w = bench.time_solo(DEC, max(10, steps))
+        r = max(1, round(solo_p_w / solo_d_w))
+        bench.run_concurrent(warmup, r, only)
+        wall_ms, pk, dk = bench.run_concurrent(steps, r, only)
+        return {"split": f"{pp}/{dp}", "prefill_cus": p_cus, "decode_cus": d_cus, "decode_per_prefill": r,
+                "ms_per_step": wall_ms,
+                "prefill_tok_s": bench.T / wall_ms * 1e3 if only != "decode" else 0.0,
+                "decode_tok_s": r * bench.B / wall_ms * 1e3 if only != "prefill" else 0.0,
+                "prefill_kernel_ms": median(pk), "decode_kernel_ms": median(dk),
+                "prefill_tflops": bench.prefill_flops / (median(pk) * 1e-3) / 1e12 if pk else None,
+                "decode_gbs": bench.decode_bytes / (median(dk) * 1e-3) / 1e9 if dk else None,
+                "solo": {"prefill_kernel_ms": solo_p_k, "prefill_step_ms": solo_p_w, "decode_kernel_ms": solo_d_k,
+                         "decode_step_ms": solo_d_w,
+                         "prefill_tflops": bench.prefill_flops / (solo_p_k * 1e-3) / 1e12,
+                         "decode_gbs": bench.decode_bytes / (solo_d_k * 1e-3) / 1e9}}
+
+    head = measure_split(p_pct, d_pct, args.steps, args.warmup, args.only)
+    splits = [head]
+    if not args.no_sweep:
+        for pp, dp in list(cfg.cu_splits) + [(100, 100)]:
+            if (pp, dp) != (p_pct, d_pct):
+                splits.append(measure_split(pp, dp, max(10, args.steps // 2), 2))
+
+    r = head["decode_per_prefill"]
+    tokens_per_step = (bench.T if args.only != "decode" else 0) + (r * bench.B if args.only != "prefill" else 0)
+    pre_ms = head["prefill_kernel_ms"]
+    result = {
+        "metric": "prefill tok/s + decode tok/s at CU split; % MFMA peak / % HBM BW",
+        "value": tokens_per_step / head["ms_per_step"] * 1e3,
+        "unit": "tokens/s (prefill + decode tokens, one attention layer)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "note": cfg.note, "prefill_batch": list(cfg.prefill_lens),
+                   "decode_batch": bench.B, "decode_ctx_mean": sum(cfg.decode_ctx) / bench.B,
+                   "q_heads": cfg.layer.n_q_heads, "kv_heads": cfg.layer.n_kv_heads, "head_dim": cfg.layer.dim_qk,
+                   "page_tokens": cfg.layer.page_tokens, "pool_pages": bench.num_pages,
+                   "cu_split": head["split"], "prefill_cus": head["prefill_cus"], "decode_cus": head["decode_cus"],
+                   "step": f"1 prefill step || {r} decode steps", "only": args.only},
+        "prefill_tok_s": head["prefill_tok_s"], "decode_tok_s": head["decode_tok_s"],
+        "roofline": {"bound": "mfma", "kernel": "prefill_kernel<128,128>", "achieved": head["prefill_tflops"],
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": (head["prefill_tflops"] or 0.0) / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel_ms": pre_ms, "flops_per_launch": bench.prefill_flops,
+                     "share_cus": head["prefill_cus"],
+                     "frac_of_share_peak": (head["prefill_tflops"] or 0.0) / (PEAK_BF16_TFLOPS * head["prefill_cus"] / bench.total_cus)},
+        "roofline_decode": {"bound": "hbm", "kernel": "decode_gqa_kernel<128> (+combine)", "achieved": head["decode_gbs"],
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": (head["decode_gbs"] or 0.0) / PEAK_HBM_GBS,
+                            "traffic": None, "kernel_ms": head["decode_kernel_ms"],
+                            "bytes_per_launch": bench.decode_bytes, "share_cus": head["decode_cus"]},
+        "splits": splits,
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(cfg, r)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

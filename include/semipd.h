@@ -193,6 +193,14 @@ int spd_phase_stream(spd_ctx* ctx, int phase, void** hip_stream_out);
 /* GPU time of the phase's most recent step in milliseconds (waits for that step). */
 int spd_phase_last_ms(spd_ctx* ctx, int phase, float* ms);
 
+/* Measurement aid.  With kernel timing on, each step brackets its attention kernel(s) (not the
+ * block-table upload or the page write) with HIP events on the phase's stream; the last
+ * 256 steps are kept.  spd_phase_kernel_ms waits for the phase, writes the durations
+ * (milliseconds, oldest first) of the steps recorded since the last call to host out[cap]
+ * and their number to *n_out.  Off by default (each record costs a few microseconds). */
+int spd_set_kernel_timing(spd_ctx* ctx, int on);
+int spd_phase_kernel_ms(spd_ctx* ctx, int phase, float* out, int32_t cap, int32_t* n_out);
+
 /* ------------------------------------------------------------------ partition
  * Paper, "Computational Resource Controller": a configuration (x, y) gives x % of the
  * compute units to prefill and y % to decode; x + y may exceed 100 (the two then compete);

@@ -110,6 +110,9 @@ extern "C" int spd_ctx_destroy(spd_ctx* ctx) {
       if (s.workspace) (void)hipFree(s.workspace);
       for (hipEvent_t e : {s.ev_start, s.ev_end, s.ev_switch, s.ev_cross})
         if (e) (void)hipEventDestroy(e);
+      for (auto& pair : s.kev)
+        for (hipEvent_t e : pair)
+          if (e) (void)hipEventDestroy(e);
     }
     for (auto& kv : ctx->stream_cache) (void)hipStreamDestroy(kv.second);
   }
@@ -244,7 +247,40 @@ int workspace_reserve(spd_ctx* ctx, int phase, size_t bytes, char** out) {
   return SPD_OK;
 }
 
+int kernel_timing_mark(spd_ctx* ctx, int phase, int which, hipStream_t stream) {
+  if (!ctx->kernel_timing) return SPD_OK;
+  spd_phase_state& s = ctx->phase[phase];
+  hipEvent_t& e = s.kev[s.kev_count % 256][which];
+  if (!e) SPD_HIP(hipEventCreate(&e));
+  SPD_HIP(hipEventRecord(e, stream));
+  if (which == 1) ++s.kev_count;
+  return SPD_OK;
+}
+
 }  // namespace spd
+
+extern "C" int spd_set_kernel_timing(spd_ctx* ctx, int on) {
+  if (!ctx) return SPD_EINVAL;
+  if (ctx->device < 0) return SPD_ESTATE;
+  ctx->kernel_timing = on != 0;
+  return SPD_OK;
+}
+
+extern "C" int spd_phase_kernel_ms(spd_ctx* ctx, int phase, float* out, int32_t cap, int32_t* n_out) {
+  if (!ctx || phase < 0 || phase > 1 || !n_out || cap < 0 || (cap > 0 && !out)) return SPD_EINVAL;
+  if (ctx->device < 0) return SPD_ESTATE;
+  int rc = spd_phase_sync(ctx, phase);
+  if (rc != SPD_OK) return rc;
+  spd_phase_state& s = ctx->phase[phase];
+  uint64_t first = s.kev_count > 256 ? s.kev_count - 256 : 0;
+  if (first < s.kev_read) first = s.kev_read;
+  int32_t n = 0;
+  for (uint64_t i = first; i < s.kev_count && n < cap; ++i, ++n)
+    SPD_HIP(hipEventElapsedTime(&out[n], s.kev[i % 256][0], s.kev[i % 256][1]));
+  s.kev_read = first + (uint64_t)n;
+  *n_out = n;
+  return SPD_OK;
+}
 
 extern "C" int spd_phase_sync(spd_ctx* ctx, int phase) {
   if (!ctx || phase < 0 || phase > 1) return SPD_EINVAL;

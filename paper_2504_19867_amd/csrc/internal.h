@@ -67,12 +67,13 @@ struct TileDesc {
   int32_t pad[3];
 };
 
-// Prefill work item: one tile of BLOCK_M query rows of one request.
+// Prefill work item = one workgroup: one tile of query rows of one request, for a group of query
+// heads that share a KV head.  len == 0 marks a padding item (the workgroup exits at once).
 struct PrefillWork {
   int32_t row0;      // first packed row of the request
   int32_t len;       // request length
-  int32_t q_tile;    // tile index inside the request
-  int32_t pad;
+  int32_t q_tile;    // tile index inside the request (tile height depends on the head grouping)
+  int32_t head0;     // first query head of the workgroup's head group
 };
 
 extern thread_local int g_last_hip_error;
@@ -116,6 +117,8 @@ struct spd_phase_state {
   bool timed = false;
   char* workspace = nullptr;           // split-K partials (decode)
   size_t ws_cap = 0;
+  hipEvent_t kev[256][2] = {};         // kernel timing ring (measurement aid)
+  uint64_t kev_count = 0, kev_read = 0;
 };
 
 struct spd_ctx {
@@ -124,6 +127,7 @@ struct spd_ctx {
   std::mutex part_mu;                  // partition state (set_partition vs step entry)
   std::map<std::vector<uint32_t>, hipStream_t> stream_cache;
   spd_phase_state phase[2];
+  bool kernel_timing = false;
 };
 
 namespace spd {
@@ -132,6 +136,7 @@ int phase_enter(spd_ctx* ctx, int phase, hipStream_t* stream_out);   // adopt pe
 int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out);
 int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream);
 int workspace_reserve(spd_ctx* ctx, int phase, size_t bytes, char** out);
+int kernel_timing_mark(spd_ctx* ctx, int phase, int which, hipStream_t stream);   // which: 0 begin, 1 end
 
 // kernel launchers (kernels_*.hip); all enqueue on `stream` and return the launch status
 hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d_tiles, int n_tiles,
@@ -146,5 +151,6 @@ hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out
                           int n_work, int H, int Hkv, int dqk, int dv, float scale, hipStream_t stream);
 hipError_t launch_probe(int32_t* d_ids, int n_blocks, hipStream_t stream);
 bool prefill_shape_supported(int dqk, int dv);
-int prefill_block_m();
+int prefill_heads_per_block(int group);   // query heads of one KV head that share a workgroup
+int prefill_block_m(int group);           // query rows per workgroup
 }  // namespace spd

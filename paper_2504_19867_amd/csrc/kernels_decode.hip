@@ -142,7 +142,8 @@ __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(
   const int tile1 = min(n_tiles, tile0 + chunk_tiles);
   const int n_steps = (tile1 - tile0 + 1) >> 1;
   const int n_chunks = (n_tiles + chunk_tiles - 1) / chunk_tiles;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: page ids become scalar loads
   const int col = lane & 15, c4 = lane >> 4;
 
   bf16x8 qf[D / 32];
@@ -160,18 +161,32 @@ __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(
 
   const int32_t* bt_row = bt + (size_t)b * bt_stride;
   const uint64_t head_off = (uint64_t)g * head_bytes;
+  // Software pipeline over this wave's steps j = wave, wave + 4, ...: the loads of the next step
+  // are in flight while the current one is consumed.  The steady-state loop body has no branch,
+  // so the compiler can wait for exactly the older buffer (vmcnt = loads of the newer one).
+#define SPD_LOAD(F, J) load_step<D>(F, pool, page_bytes, tile_bytes, tiles_per_page, bt_row, head_off, tile0 + 2 * (J), n_tiles, lane)
+#define SPD_COMP(F, J) compute_step<D>(F, qf, O, m, l, tile0 + 2 * (J), n_tiles, n, c, c4)
   TileFrag<D> fa, fb;
   int j = wave;
-  if (j < n_steps) load_step<D>(fa, pool, page_bytes, tile_bytes, tiles_per_page, bt_row, head_off, tile0 + 2 * j, n_tiles, lane);
-  for (; j < n_steps; j += 8) {
-    const bool has_b = j + 4 < n_steps;
-    if (has_b) load_step<D>(fb, pool, page_bytes, tile_bytes, tiles_per_page, bt_row, head_off, tile0 + 2 * (j + 4), n_tiles, lane);
-    compute_step<D>(fa, qf, O, m, l, tile0 + 2 * j, n_tiles, n, c, c4);
-    if (has_b) {
-      if (j + 8 < n_steps) load_step<D>(fa, pool, page_bytes, tile_bytes, tiles_per_page, bt_row, head_off, tile0 + 2 * (j + 8), n_tiles, lane);
-      compute_step<D>(fb, qf, O, m, l, tile0 + 2 * (j + 4), n_tiles, n, c, c4);
+  if (j < n_steps) {
+    SPD_LOAD(fa, j);
+    while (j + 8 < n_steps) {
+      SPD_LOAD(fb, j + 4);
+      SPD_COMP(fa, j);
+      SPD_LOAD(fa, j + 8);
+      SPD_COMP(fb, j + 4);
+      j += 8;
+    }
+    if (j + 4 < n_steps) {
+      SPD_LOAD(fb, j + 4);
+      SPD_COMP(fa, j);
+      SPD_COMP(fb, j + 4);
+    } else {
+      SPD_COMP(fa, j);
     }
   }
+#undef SPD_LOAD
+#undef SPD_COMP
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
 

@@ -5,17 +5,25 @@
 //     out[i,h,:] = sum_{j<=i} softmax_j(scale * q[i,h,:] . k[j,g,:]) * v[j,g,:]
 // (The page write of K, V that belongs to the same step is kv_write_kernel.)
 //
-// A dense contraction, so it runs on the matrix cores.  One workgroup = 4 waves = one tile of
-// 128 query rows of one head; each wave owns 32 rows.  Everything is kept TRANSPOSED so that a
-// query is a lane (column), not a row:
-//     S^T[key, query] = K_tile[64 x d] . Q^T[d x 32]     v_mfma_f32_32x32x16_bf16
+// A dense contraction, so it runs on the matrix cores.  One workgroup = 8 waves = one CU's worth
+// of work; every wave owns 32 query rows of one head.  The 8 waves are HB query heads of ONE
+// KV head (grouped-query attention: they all need the same K, V) times 8 / HB row sub-tiles,
+// so each K/V tile fetched into LDS feeds 256 (row, head) pairs.
+//
+// Everything is kept TRANSPOSED so that a query is a lane (column), not a row:
+//     S^T[key, query] = K_tile[64 x d] . Q^T[d x 32]          v_mfma_f32_32x32x16_bf16
 //     O^T[dim, query] += V_tile^T[dv x 64] . P^T[64 x 32]
 // With queries along lanes the softmax statistics (running max, running sum, rescale factor)
 // are per-lane scalars, the row maximum needs one cross-lane exchange per tile (lane ^ 32), and
-// the S^T accumulators are already in the B-operand order of the second product - P never
-// leaves registers.  Q^T fragments live in registers for the whole workgroup; K and V tiles
-// of 64 keys are staged through LDS (K row-padded, V transposed in registers on the way in and
-// stored with an XOR swizzle) so that every operand read is a conflict-free 16-byte read.
+// the S^T accumulators are already in the B-operand order of the second product: P never
+// leaves registers.  Q^T fragments live in registers for the whole workgroup.
+//
+// K and V tiles of 64 keys stream from global memory straight into a ring of LDS stages with
+// global_load_lds_dwordx4 (no register staging, no LDS stores), PD tiles ahead of the compute;
+// one s_barrier per tile.  K rows are read back with 16-byte reads in A-operand order; V stays
+// in its natural [key][dim] order and the transposition that the second product needs is done
+// by the LDS transpose read ds_read_b64_tr_b16.  Both tiles are XOR-swizzled at 16-byte
+// granularity against bank conflicts.
 #include "internal.h"
 
 namespace spd {
@@ -25,140 +33,179 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 128;   // query rows per workgroup
-constexpr int BN = 64;    // keys per LDS tile
+constexpr int BN = 64;        // keys per LDS tile
+constexpr int WAVES = 8;      // waves per workgroup
 
 __device__ inline uint32_t cvt_pk_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
 }
 
-// Position of key offset o (0..15) inside its 16-key group of the transposed V tile: the order
-// in which the S^T accumulator registers of one lane enumerate keys (bits 2 and 3 swapped).
-__device__ inline int vt_unit_swizzle(int d) { return (d & 7) ^ ((d >> 3) & 7); }
+// 16 bytes per lane from global memory to LDS: lane i's data lands at lds_byte_addr + 16 * i.
+// The compiler does not see this write; completion is tracked by hand with vmcnt (below).
+__device__ inline void dma16(const void* gptr, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte_addr), "v"(gptr) : "memory");
+}
+// s_waitcnt vmcnt(N) only (expcnt and lgkmcnt fields left at their maxima)
+#define SPD_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
 
-template <int DQK, int DV>
-__global__ __launch_bounds__(256, 2) void prefill_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+// XOR swizzles (in units of 16-byte chunks) of a K row and a V row
+template <int DQK> __device__ inline int k_swz(int row) { return DQK == 128 ? (row & 15) : ((row >> 1) & 7); }
+template <int DV> __device__ inline int v_swz(int row) { return DV == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1); }
+
+template <int DQK, int DV, int HB>
+__global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                          const bf16_t* __restrict__ v, bf16_t* __restrict__ out,
                                                          const PrefillWork* __restrict__ work, int H, int Hkv,
                                                          float c /* scale * log2(e) */) {
-  constexpr int KROW = DQK + 8;                 // padded K row (elements): consecutive rows shift by 4 banks
-  constexpr int KCH = DQK / 8;                  // 16-byte chunks per K row
-  constexpr int K_LD = (BN * KCH) / 256;        // 16-byte global loads per thread for the K tile
-  constexpr int VCH = DV / 8;
-  constexpr int V_ITEMS = (BN / 4) * VCH;       // (key quad, 8-dim chunk) items of the V tile
-  constexpr int V_LD = (V_ITEMS + 255) / 256;
-  static_assert((BN * KCH) % 256 == 0, "K tile does not divide over 256 threads");
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[BN * KROW];
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[DV * BN];
+  constexpr int QS = WAVES / HB;                // 32-row sub-tiles per workgroup
+  constexpr int CHK = DQK / 8, CHV = DV / 8;    // 16-byte chunks per K / V row
+  constexpr int K_BYTES = BN * DQK * 2, V_BYTES = BN * DV * 2, STAGE_BYTES = K_BYTES + V_BYTES;
+  constexpr int NSTAGE = DQK > 128 ? 3 : 4;     // LDS ring
+  constexpr int PD = NSTAGE - 1;                // tiles in flight ahead of the compute
+  constexpr int NI = CHK + CHV;                 // 1 KiB load instructions per tile
+  static_assert(NI % WAVES == 0, "tile loads must divide evenly over the waves");
+  constexpr int LPW = NI / WAVES;               // load instructions per wave per tile
+  constexpr int KS = DQK / 16, VB = DV / 32;
+  constexpr int NS = 2 * KS;                    // MFMAs of S^T
+  constexpr int RING = 8;                       // K operands in flight
+  static_assert(NS >= RING, "operand ring longer than the first product");
+  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE_BYTES];
 
-  const PrefillWork w = work[blockIdx.x / H];
-  const int h = blockIdx.x % H;
-  const int g = h / (H / Hkv);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const PrefillWork w = work[blockIdx.x];
+  if (w.len <= 0) return;                       // padding item
+  const int G = H / Hkv;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n32 = lane & 31, hh = lane >> 5;
-  const int q_start = w.q_tile * BM;
-  const int wave_q0 = q_start + 32 * wave;
-  const int qi = wave_q0 + n32;                                  // this lane's query (row inside the request)
+  const int h = w.head0 + wave % HB;
+  const int g = w.head0 / G;
+  const int q_start = w.q_tile * (32 * QS);
+  const int wave_q0 = q_start + 32 * (wave / HB);
+  const bool wave_active = wave_q0 < w.len;     // waves past the prompt's end only help loading
+  const int qi = wave_q0 + n32;                 // this lane's query (row inside the request)
   const int qi_c = qi < w.len ? qi : w.len - 1;
 
   // Q^T fragments (B operand: column = query, 8 consecutive dims per lane and k-step)
-  bf16x8 qf[DQK / 16];
+  bf16x8 qf[KS];
   {
     const bf16_t* qp = q + ((size_t)(w.row0 + qi_c) * H + h) * DQK + 8 * hh;
 #pragma unroll
-    for (int s = 0; s < DQK / 16; ++s) qf[s] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * s));
+    for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * s));
   }
 
-  f32x16 O[DV / 32];
+  const int kv_end = min(w.len, q_start + 32 * QS);
+  const int n_kv_tiles = (kv_end + BN - 1) / BN;
+  const char* kbase = (const char*)(k + ((size_t)w.row0 * Hkv + g) * DQK);
+  const char* vbase = (const char*)(v + ((size_t)w.row0 * Hkv + g) * DV);
+  const uint32_t k_pitch = (uint32_t)Hkv * DQK * 2, v_pitch = (uint32_t)Hkv * DV * 2;
+  const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+
+  // ---- tile loads.  Load instruction ii = wave + 8 j (j < LPW) fills the 64 consecutive 16-byte
+  // slots [64 ii, 64 ii + 64) of the stage: K slots first (row = slot / CHK), then V slots.
+  // Slot s of a row holds the row's chunk s ^ swz(row).
+  int ld_row[LPW], ld_coff[LPW];                // tile row and byte offset inside the global row
 #pragma unroll
-  for (int i = 0; i < DV / 32; ++i)
+  for (int j = 0; j < LPW; ++j) {
+    const int ii = wave + WAVES * j;
+    if (ii < CHK) {
+      const int slot = ii * 64 + lane, row = slot / CHK, sl = slot % CHK;
+      ld_row[j] = row;
+      ld_coff[j] = (sl ^ k_swz<DQK>(row)) * 16;
+    } else {
+      const int slot = (ii - CHK) * 64 + lane, row = slot / CHV, sl = slot % CHV;
+      ld_row[j] = row;
+      ld_coff[j] = (sl ^ v_swz<DV>(row)) * 16;
+    }
+  }
+  auto issue_loads = [&](int kt) {
+    const int kv0 = kt * BN;
+    const uint32_t stage = smem_base + (uint32_t)(kt % NSTAGE) * STAGE_BYTES;
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) {
+      const int ii = wave + WAVES * j;
+      const int key = min(kv0 + ld_row[j], w.len - 1);          // rows past the prompt re-read its last row
+      const char* src = (ii < CHK) ? kbase + (size_t)key * k_pitch + ld_coff[j] : vbase + (size_t)key * v_pitch + ld_coff[j];
+      dma16(src, stage + (uint32_t)ii * 1024);
+    }
+  };
+
+  // ---- LDS operand addresses (byte offsets inside a stage)
+  // K operand (S^T block b, k-step ks): row 32 b + n32, chunk 2 ks + hh
+  int k_off[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_off[ks] = n32 * (CHK * 16) + (((2 * ks + hh) ^ k_swz<DQK>(n32)) * 16);
+  // V operand (16-key step kk, value block blk): two transpose reads.  In each group of 16 lanes
+  // lane r supplies row (key) 4 hh + r / 4 and dims 4 (r % 4) .. + 3 of the group's 16 dims; the
+  // hardware hands lane i of the group dim i of those 4 keys.
+  const int r16 = lane & 15;
+  const int v_row = 4 * hh + (r16 >> 2);                         // plus 16 kk + 8 half
+  int v_off[VB];
+#pragma unroll
+  for (int blk = 0; blk < VB; ++blk) {
+    const int dim = 32 * blk + 16 * ((lane >> 4) & 1) + 4 * (r16 & 3);
+    v_off[blk] = K_BYTES + v_row * (CHV * 16) + (((dim >> 3) ^ v_swz<DV>(v_row)) * 16) + (dim & 7) * 2;
+  }
+
+  f32x16 O[VB];
+#pragma unroll
+  for (int i = 0; i < VB; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) O[i][e] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  const int kv_end = min(w.len, q_start + BM);
-  const int n_kv_tiles = (kv_end + BN - 1) / BN;
-  const bf16_t* kbase = k + ((size_t)w.row0 * Hkv + g) * DQK;
-  const bf16_t* vbase = v + ((size_t)w.row0 * Hkv + g) * DV;
+#pragma unroll
+  for (int t = 0; t < PD; ++t)
+    if (t < n_kv_tiles) issue_loads(t);
 
-  uint4 kreg[K_LD], vreg[V_LD][4];
-  auto load_tile = [&](int kt) {
-    const int kv0 = kt * BN;
-#pragma unroll
-    for (int p = 0; p < K_LD; ++p) {
-      const int idx = p * 256 + tid, row = idx / KCH, ch = idx % KCH;
-      const int key = min(kv0 + row, w.len - 1);
-      kreg[p] = *(const uint4*)(kbase + (size_t)key * Hkv * DQK + 8 * ch);
-    }
-#pragma unroll
-    for (int p = 0; p < V_LD; ++p) {
-      const int idx = p * 256 + tid, kq = idx / VCH, dc = idx % VCH;
-      if (V_ITEMS % 256 != 0 && idx >= V_ITEMS) break;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int key = min(kv0 + 4 * kq + t, w.len - 1);
-        vreg[p][t] = *(const uint4*)(vbase + (size_t)key * Hkv * DV + 8 * dc);
-      }
-    }
-  };
-  auto store_tile = [&]() {
-#pragma unroll
-    for (int p = 0; p < K_LD; ++p) {
-      const int idx = p * 256 + tid, row = idx / KCH, ch = idx % KCH;
-      *(uint4*)(Ks + row * KROW + 8 * ch) = kreg[p];
-    }
-#pragma unroll
-    for (int p = 0; p < V_LD; ++p) {
-      const int idx = p * 256 + tid, kq = idx / VCH, dc = idx % VCH;
-      if (V_ITEMS % 256 != 0 && idx >= V_ITEMS) break;
-      // keys 4kq..4kq+3 sit at 4 consecutive positions of row d: 16*(kq/4) + 8*(kq&1) + 4*((kq>>1)&1)
-      const int pos4 = 16 * (kq >> 2) + 8 * (kq & 1) + 4 * ((kq >> 1) & 1);
-      const uint32_t* r0 = (const uint32_t*)&vreg[p][0];
-      const uint32_t* r1 = (const uint32_t*)&vreg[p][1];
-      const uint32_t* r2 = (const uint32_t*)&vreg[p][2];
-      const uint32_t* r3 = (const uint32_t*)&vreg[p][3];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int d = 8 * dc + e;
-        uint2 o;
-        if (e & 1) {
-          o.x = (r0[e >> 1] >> 16) | (r1[e >> 1] & 0xffff0000u);
-          o.y = (r2[e >> 1] >> 16) | (r3[e >> 1] & 0xffff0000u);
-        } else {
-          o.x = (r0[e >> 1] & 0xffffu) | (r1[e >> 1] << 16);
-          o.y = (r2[e >> 1] & 0xffffu) | (r3[e >> 1] << 16);
-        }
-        const int unit = (pos4 >> 3) ^ vt_unit_swizzle(d);
-        *(uint2*)(Vt + d * BN + unit * 8 + (pos4 & 7)) = o;
-      }
-    }
-  };
-
-  load_tile(0);
   for (int kt = 0; kt < n_kv_tiles; ++kt) {
     const int kv0 = kt * BN;
-    __syncthreads();                 // everyone is done reading the previous tile
-    store_tile();
-    __syncthreads();
-    if (kt + 1 < n_kv_tiles) load_tile(kt + 1);
-    if (kv0 > wave_q0 + 31) continue;          // every key of the tile is in this wave's future
+    // this wave's loads of tile kt are done when at most (tiles issued after kt) * LPW remain
+    const int later = min(PD - 1, n_kv_tiles - 1 - kt);
+    if (later >= 2) SPD_WAIT_VMCNT(2 * LPW);
+    else if (later == 1) SPD_WAIT_VMCNT(LPW);
+    else SPD_WAIT_VMCNT(0);
+    // all waves: tile kt has landed, and everyone is done with tile kt - 1, whose stage is refilled next
+    asm volatile("s_barrier" ::: "memory");
+    if (kt + PD < n_kv_tiles) issue_loads(kt + PD);
+    if (!wave_active || kv0 > wave_q0 + 31) continue;          // every key of the tile is in this wave's future
 
-    // ---- S^T = K . Q^T : two 32-key blocks
+    const char* stage = smem + (kt % NSTAGE) * STAGE_BYTES;
+    auto read_k = [&](int i) -> uint4 { return *(const uint4*)(stage + k_off[i / 2] + (i % 2) * (32 * CHK * 16)); };
+    auto read_v = [&](int i, int half) -> s16x4 {
+      const int kk = i / VB, blk = i % VB;
+      return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(stage + v_off[blk] + (16 * kk + 8 * half) * (CHV * 16)));
+    };
+
+    // ---- S^T = K . Q^T.  Operand i: block b = i % 2 (32 keys), k-step ks = i / 2; LDS reads run
+    // RING operands ahead of the MFMAs that consume them.
     f32x16 S[2];
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int e = 0; e < 16; ++e) S[b][e] = 0.f;
-      const bf16_t* kp = Ks + (32 * b + n32) * KROW + 8 * hh;
+    uint4 ring[RING];
 #pragma unroll
-      for (int s = 0; s < DQK / 16; ++s) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, *(const uint4*)(kp + 16 * s));
-        S[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], S[b], 0, 0, 0);
-      }
+    for (int i = 0; i < RING; ++i) ring[i] = read_k(i);
+    __builtin_amdgcn_sched_barrier(0);          // keep the issue order below: the scheduler would
+#pragma unroll                                  // otherwise sink every read next to its use
+    for (int i = 0; i < NS; ++i) {
+      S[i % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[i % RING]), qf[i / 2], S[i % 2], 0, 0, 0);
+      if (i + RING < NS) ring[i % RING] = read_k(i + RING);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    // first V operands: in flight while the vector units do the softmax
+    s16x4 vr[2][VB][2];                         // [parity of kk][value block][half]
+#pragma unroll
+    for (int blk = 0; blk < VB; ++blk) {
+      vr[0][blk][0] = read_v(blk, 0);
+      vr[0][blk][1] = read_v(blk, 1);
+    }
+
     // lane holds, for query qi, keys kv0 + 32b + 8*(i/4) + 4*hh + i%4
-    if (kv0 + BN - 1 > wave_q0) {              // tile crosses this wave's diagonal (or the prompt's end)
+    if (kv0 + BN - 1 > wave_q0) {               // tile crosses this wave's diagonal (or the prompt's end)
 #pragma unroll
       for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -172,7 +219,6 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const bf16_t* __restric
     for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[1][i]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float m_new = fmaxf(m, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
     const float mc = m_new * c;
     float psum = 0.f;
     uint32_t pb[2][8];
@@ -185,35 +231,46 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const bf16_t* __restric
         psum += p0 + p1;
         pb[b][i >> 1] = cvt_pk_bf16(p0, p1);
       }
-    l = l * alpha + psum;
-    m = m_new;
+    // the running maximum rarely moves after the first tiles: rescale only when some lane needs it
+    if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
+      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+      l *= alpha;
 #pragma unroll
-    for (int blk = 0; blk < DV / 32; ++blk)
+      for (int blk = 0; blk < VB; ++blk)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) O[blk][e] *= alpha;
+        for (int e = 0; e < 16; ++e) O[blk][e] *= alpha;
+      m = m_new;
+    }
+    l += psum;
 
-    // ---- O^T += V^T . P^T : four 16-key steps; step kk uses S^T block kk/2, registers 8*(kk%2)..+7
+    // ---- O^T += V^T . P^T : 16-key step kk multiplies with S^T block kk/2, registers 8*(kk%2) .. +7;
+    // the operands of step kk + 1 are read while step kk multiplies
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kk = 0; kk < BN / 16; ++kk) {
       const uint4 praw = uint4{pb[kk >> 1][4 * (kk & 1)], pb[kk >> 1][4 * (kk & 1) + 1], pb[kk >> 1][4 * (kk & 1) + 2],
                                pb[kk >> 1][4 * (kk & 1) + 3]};
-      const bf16x8 pfrag = __builtin_bit_cast(bf16x8, praw);
 #pragma unroll
-      for (int blk = 0; blk < DV / 32; ++blk) {
-        const int d = 32 * blk + n32;
-        const int unit = (2 * kk + hh) ^ vt_unit_swizzle(d);
-        const bf16x8 a = __builtin_bit_cast(bf16x8, *(const uint4*)(Vt + d * BN + unit * 8));
-        O[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pfrag, O[blk], 0, 0, 0);
+      for (int blk = 0; blk < VB; ++blk) {
+        const uint2 lo = __builtin_bit_cast(uint2, vr[kk & 1][blk][0]), hi = __builtin_bit_cast(uint2, vr[kk & 1][blk][1]);
+        const uint4 a = uint4{lo.x, lo.y, hi.x, hi.y};
+        O[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, praw),
+                                                         O[blk], 0, 0, 0);
+        if (kk + 1 < BN / 16) {
+          vr[(kk + 1) & 1][blk][0] = read_v((kk + 1) * VB + blk, 0);
+          vr[(kk + 1) & 1][blk][1] = read_v((kk + 1) * VB + blk, 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
 
   l += __shfl_xor(l, 32);
-  if (qi < w.len) {
+  if (wave_active && qi < w.len) {
     const float inv = 1.f / l;
     bf16_t* op = out + ((size_t)(w.row0 + qi) * H + h) * DV + 4 * hh;
 #pragma unroll
-    for (int blk = 0; blk < DV / 32; ++blk)
+    for (int blk = 0; blk < VB; ++blk)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         uint2 pk;
@@ -227,20 +284,35 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const bf16_t* __restric
 bool prefill_shape_supported(int dqk, int dv) {
   return (dqk == 64 && dv == 64) || (dqk == 128 && dv == 128) || (dqk == 192 && dv == 128);
 }
-int prefill_block_m() { return BM; }
+
+// Query heads of one KV head that share a workgroup: the largest of 8, 4, 2, 1 dividing the group size.
+int prefill_heads_per_block(int group) {
+  for (int hb = WAVES; hb > 1; hb >>= 1)
+    if (group % hb == 0) return hb;
+  return 1;
+}
+int prefill_block_m(int group) { return 32 * (WAVES / prefill_heads_per_block(group)); }
+
+template <int DQK, int DV>
+static void launch_hb(int hb, dim3 grid, hipStream_t stream, const bf16_t* q, const bf16_t* k, const bf16_t* v,
+                      bf16_t* out, const PrefillWork* work, int H, int Hkv, float c) {
+  const dim3 block(64 * WAVES);
+  if (hb == 8) hipLaunchKernelGGL((prefill_kernel<DQK, DV, 8>), grid, block, 0, stream, q, k, v, out, work, H, Hkv, c);
+  else if (hb == 4) hipLaunchKernelGGL((prefill_kernel<DQK, DV, 4>), grid, block, 0, stream, q, k, v, out, work, H, Hkv, c);
+  else if (hb == 2) hipLaunchKernelGGL((prefill_kernel<DQK, DV, 2>), grid, block, 0, stream, q, k, v, out, work, H, Hkv, c);
+  else hipLaunchKernelGGL((prefill_kernel<DQK, DV, 1>), grid, block, 0, stream, q, k, v, out, work, H, Hkv, c);
+}
 
 hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out, const PrefillWork* d_work, int n_work,
                           int H, int Hkv, int dqk, int dv, float scale, hipStream_t stream) {
   const float c = scale * 1.4426950408889634f;
-  const dim3 grid((unsigned)n_work * (unsigned)H), block(256);
-#define SPD_LAUNCH(DQ, DVV)                                                                                         \
-  hipLaunchKernelGGL((prefill_kernel<DQ, DVV>), grid, block, 0, stream, (const bf16_t*)q, (const bf16_t*)k,          \
-                     (const bf16_t*)v, (bf16_t*)out, d_work, H, Hkv, c)
-  if (dqk == 64 && dv == 64) SPD_LAUNCH(64, 64);
-  else if (dqk == 128 && dv == 128) SPD_LAUNCH(128, 128);
-  else if (dqk == 192 && dv == 128) SPD_LAUNCH(192, 128);
+  const int hb = prefill_heads_per_block(H / Hkv);
+  const dim3 grid((unsigned)n_work);
+  const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v;
+  if (dqk == 64 && dv == 64) launch_hb<64, 64>(hb, grid, stream, qq, kk, vv, (bf16_t*)out, d_work, H, Hkv, c);
+  else if (dqk == 128 && dv == 128) launch_hb<128, 128>(hb, grid, stream, qq, kk, vv, (bf16_t*)out, d_work, H, Hkv, c);
+  else if (dqk == 192 && dv == 128) launch_hb<192, 128>(hb, grid, stream, qq, kk, vv, (bf16_t*)out, d_work, H, Hkv, c);
   else return hipErrorInvalidValue;
-#undef SPD_LAUNCH
   return hipGetLastError();
 }
 

@@ -2,6 +2,7 @@
 // reservation, block-table staging, launch geometry.  All arithmetic of the method runs in
 // the kernels (kernels_*.hip).
 #include "internal.h"
+#include "prefill_work.h"
 
 #include <stdlib.h>
 #include <string.h>
@@ -98,14 +99,8 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   }
   if (ctx->device < 0) return SPD_ESTATE;
 
-  const int BM = prefill_block_m();
   std::vector<PrefillWork> work;
-  for (int r = 0; r < b->n_req; ++r) {
-    int32_t row0 = b->cu_seqlens[r], len = b->cu_seqlens[r + 1] - row0;
-    for (int32_t t = 0; t < (len + BM - 1) / BM; ++t) work.push_back(PrefillWork{row0, len, t, 0});
-  }
-  // causal work grows with the tile index: heaviest tiles first
-  std::stable_sort(work.begin(), work.end(), [](const PrefillWork& a, const PrefillWork& c) { return a.q_tile > c.q_tile; });
+  build_prefill_work(b->cu_seqlens, b->n_req, b->n_q_heads, b->n_kv_heads, ctx->xcds, work);
 
   hipStream_t stream;
   int rc = phase_enter(ctx, SPD_PHASE_PREFILL, &stream);
@@ -140,8 +135,10 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   const void* page_src_v = g.kind == SPD_KV_GQA ? b->v : nullptr;
   SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(st->dev + off_desc), (int)descs.size(), page_src_k,
                           page_src_v, stream));
+  if ((rc = kernel_timing_mark(ctx, SPD_PHASE_PREFILL, 0, stream)) != SPD_OK) return rc;
   SPD_HIP(launch_prefill(b->q, b->k, b->v, b->out, (const PrefillWork*)st->dev, (int)work.size(), b->n_q_heads,
                          b->n_kv_heads, b->dim_qk, b->dim_v, b->scale, stream));
+  if ((rc = kernel_timing_mark(ctx, SPD_PHASE_PREFILL, 1, stream)) != SPD_OK) return rc;
   SPD_HIP(hipEventRecord(ps.ev_end, stream));
   ps.timed = true;
   return SPD_OK;
@@ -240,9 +237,11 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
   if ((rc = stage_commit(ctx, SPD_PHASE_DECODE, st, bytes, stream)) != SPD_OK) return rc;
   if (append)
     SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(st->dev + off_desc), B, b->k_new, b->v_new, stream));
+  if ((rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 0, stream)) != SPD_OK) return rc;
   SPD_HIP(launch_decode_gqa(g, pool->base, b->q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
                             bt_stride, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks, (float*)ws,
                             (float*)(ws ? ws + ws_o_bytes : nullptr), stream));
+  if ((rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 1, stream)) != SPD_OK) return rc;
   SPD_HIP(hipEventRecord(ds.ev_end, stream));
   ds.timed = true;
   return SPD_OK;

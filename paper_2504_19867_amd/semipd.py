@@ -24,7 +24,7 @@ EXPORTS = [
     "spd_kv_free_list", "spd_kv_write", "spd_kv_gather", "spd_prefill_step", "spd_decode_step",
     "spd_phase_sync", "spd_phase_query", "spd_phase_wait_for", "spd_phase_stream", "spd_phase_last_ms",
     "spd_set_partition", "spd_get_partition", "spd_phase_cu_mask", "spd_partition_masks",
-    "spd_phase_probe_cus", "spd_strerror", "spd_last_hip_error",
+    "spd_phase_probe_cus", "spd_strerror", "spd_last_hip_error", "spd_set_kernel_timing", "spd_phase_kernel_ms",
 ]
 
 
@@ -89,6 +89,8 @@ def _load() -> C.CDLL:
         "spd_partition_masks": [C.c_int, C.c_int, C.c_int, C.c_int, P(C.c_uint32), P(C.c_uint32), P(C.c_int), P(C.c_int)],
         "spd_phase_probe_cus": [vp, C.c_int, i32, P(i32), i32, P(i32)],
         "spd_last_hip_error": [],
+        "spd_set_kernel_timing": [vp, C.c_int],
+        "spd_phase_kernel_ms": [vp, C.c_int, P(C.c_float), i32, P(i32)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -181,6 +183,15 @@ class Context:
         _check(lib.spd_phase_last_ms(self.h, phase, C.byref(ms)), "spd_phase_last_ms")
         return ms.value
 
+    def set_kernel_timing(self, on: bool) -> None:
+        _check(lib.spd_set_kernel_timing(self.h, int(on)), "spd_set_kernel_timing")
+
+    def phase_kernel_ms(self, phase: int) -> List[float]:
+        buf = (C.c_float * 256)()
+        n = C.c_int32()
+        _check(lib.spd_phase_kernel_ms(self.h, phase, buf, 256, C.byref(n)), "spd_phase_kernel_ms")
+        return [float(buf[i]) for i in range(n.value)]
+
     def phase_probe_cus(self, phase: int, n_blocks: int = 4096) -> List[int]:
         ids = (C.c_int32 * 2048)()
         n = C.c_int32()
@@ -270,6 +281,20 @@ class Pool:
         b = spd_prefill_batch(n, ids, cu, _ptr(q), _ptr(k), _ptr(v), _ptr(latent), _ptr(out), n_q_heads,
                               n_kv_heads, dim_qk, dim_v, scale)
         _check(lib.spd_prefill_step(self.ctx.h, self.h, C.byref(b)), "spd_prefill_step")
+
+    def make_prefill_batch(self, req_ids: Sequence[int], cu_seqlens: Sequence[int], q, k, v, out, n_q_heads: int,
+                           n_kv_heads: int, dim_qk: int, dim_v: int, scale: float, latent=None):
+        """Marshal once; the returned object can be passed to prefill_step_batch repeatedly."""
+        n = len(req_ids)
+        ids = (C.c_uint64 * n)(*req_ids)
+        cu = (C.c_int32 * (n + 1))(*[int(x) for x in cu_seqlens])
+        b = spd_prefill_batch(n, ids, cu, _ptr(q), _ptr(k), _ptr(v), _ptr(latent), _ptr(out), n_q_heads,
+                              n_kv_heads, dim_qk, dim_v, scale)
+        b._keep = (ids, cu, q, k, v, out, latent)
+        return b
+
+    def prefill_step_batch(self, batch) -> None:
+        _check(lib.spd_prefill_step(self.ctx.h, self.h, C.byref(batch)), "spd_prefill_step")
 
     def make_decode_batch(self, req_ids: Sequence[int], ctx_lens: Sequence[int], q, out, n_q_heads: int,
                           scale: float, k_new=None, v_new=None):
