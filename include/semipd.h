@@ -201,6 +201,12 @@ int spd_phase_last_ms(spd_ctx* ctx, int phase, float* ms);
 int spd_set_kernel_timing(spd_ctx* ctx, int on);
 int spd_phase_kernel_ms(spd_ctx* ctx, int phase, float* out, int32_t cap, int32_t* n_out);
 
+/* Measurement aid: a plain device-to-device copy kernel (16 bytes per lane, grid-stride) of
+ * `bytes` (a multiple of 16) from src to dst on the phase's current stream.  Its known traffic
+ * calibrates hardware byte counters, and its speed on a masked stream is the streaming ceiling
+ * of that CU share. */
+int spd_phase_copy(spd_ctx* ctx, int phase, void* dst, const void* src, uint64_t bytes);
+
 /* ------------------------------------------------------------------ partition
  * Paper, "Computational Resource Controller": a configuration (x, y) gives x % of the
  * compute units to prefill and y % to decode; x + y may exceed 100 (the two then compete);

@@ -328,6 +328,16 @@ extern "C" int spd_phase_last_ms(spd_ctx* ctx, int phase, float* ms) {
   return SPD_OK;
 }
 
+extern "C" int spd_phase_copy(spd_ctx* ctx, int phase, void* dst, const void* src, uint64_t bytes) {
+  if (!ctx || phase < 0 || phase > 1 || !dst || !src || bytes == 0 || bytes % 16 != 0) return SPD_EINVAL;
+  if (((uintptr_t)dst | (uintptr_t)src) & 15) return SPD_EINVAL;
+  hipStream_t stream;
+  int rc = phase_enter(ctx, phase, &stream);
+  if (rc != SPD_OK) return rc;
+  SPD_HIP(launch_copy(dst, src, bytes, ctx->phase[phase].active_cus, stream));
+  return SPD_OK;
+}
+
 extern "C" int spd_phase_probe_cus(spd_ctx* ctx, int phase, int32_t n_blocks, int32_t* ids, int32_t cap,
                                    int32_t* n_ids) {
   if (!ctx || phase < 0 || phase > 1 || n_blocks <= 0 || n_blocks > (1 << 20) || !ids || cap <= 0 || !n_ids)

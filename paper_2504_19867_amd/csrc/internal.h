@@ -150,6 +150,7 @@ hipError_t launch_decode_gqa(const PoolGeom& g, const char* pool_base, const voi
 hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out, const PrefillWork* d_work,
                           int n_work, int H, int Hkv, int dqk, int dv, float scale, hipStream_t stream);
 hipError_t launch_probe(int32_t* d_ids, int n_blocks, hipStream_t stream);
+hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, int cus, hipStream_t stream);
 bool prefill_shape_supported(int dqk, int dv);
 int prefill_heads_per_block(int group);   // query heads of one KV head that share a workgroup
 int prefill_block_m(int group);           // query rows per workgroup

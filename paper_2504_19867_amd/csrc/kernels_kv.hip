@@ -102,6 +102,17 @@ __global__ void probe_kernel(int32_t* __restrict__ ids) {
   }
 }
 
+// Plain streaming copy, 16 bytes per lane, grid-stride.
+__global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, uint64_t n16) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, int cus, hipStream_t stream) {
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)cus * 16), dim3(256), 0, stream, (uint4*)dst, (const uint4*)src, bytes / 16);
+  return hipGetLastError();
+}
+
 hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d_tiles, int n_tiles, const void* k,
                            const void* v, hipStream_t stream) {
   if (n_tiles <= 0) return hipSuccess;

@@ -24,7 +24,7 @@ EXPORTS = [
     "spd_kv_free_list", "spd_kv_write", "spd_kv_gather", "spd_prefill_step", "spd_decode_step",
     "spd_phase_sync", "spd_phase_query", "spd_phase_wait_for", "spd_phase_stream", "spd_phase_last_ms",
     "spd_set_partition", "spd_get_partition", "spd_phase_cu_mask", "spd_partition_masks",
-    "spd_phase_probe_cus", "spd_strerror", "spd_last_hip_error", "spd_set_kernel_timing", "spd_phase_kernel_ms",
+    "spd_phase_probe_cus", "spd_strerror", "spd_last_hip_error", "spd_set_kernel_timing", "spd_phase_kernel_ms", "spd_phase_copy",
 ]
 
 
@@ -89,6 +89,7 @@ def _load() -> C.CDLL:
         "spd_partition_masks": [C.c_int, C.c_int, C.c_int, C.c_int, P(C.c_uint32), P(C.c_uint32), P(C.c_int), P(C.c_int)],
         "spd_phase_probe_cus": [vp, C.c_int, i32, P(i32), i32, P(i32)],
         "spd_last_hip_error": [],
+        "spd_phase_copy": [vp, C.c_int, vp, vp, u64],
         "spd_set_kernel_timing": [vp, C.c_int],
         "spd_phase_kernel_ms": [vp, C.c_int, P(C.c_float), i32, P(i32)],
     }
@@ -182,6 +183,9 @@ class Context:
         ms = C.c_float()
         _check(lib.spd_phase_last_ms(self.h, phase, C.byref(ms)), "spd_phase_last_ms")
         return ms.value
+
+    def phase_copy(self, phase: int, dst, src, nbytes: int) -> None:
+        _check(lib.spd_phase_copy(self.h, phase, _ptr(dst), _ptr(src), nbytes), "spd_phase_copy")
 
     def set_kernel_timing(self, on: bool) -> None:
         _check(lib.spd_set_kernel_timing(self.h, int(on)), "spd_set_kernel_timing")
