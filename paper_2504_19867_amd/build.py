@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsemipd.so")
-SOURCES = ["pool.cpp", "ctx.cpp", "steps.cpp", "kernels_kv.hip", "kernels_decode.hip", "kernels_prefill.hip"]
+SOURCES = ["pool.cpp", "ctx.cpp", "steps.cpp", "kernels_kv.hip", "kernels_decode.hip", "kernels_decode_mla.hip",
+           "kernels_prefill.hip"]
 # packed fp32 VALU forms are switched off for all device code
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -29,7 +29,8 @@ namespace spd {
 //       contiguous and holds the A operands (row = d, 4 consecutive tokens per lane) of two
 //       v_mfma_f32_16x16x16_bf16 for the value blocks 2*blk2 and 2*blk2 + 1.
 //
-// An MLA latent page holds P/16 tiles of 16 tokens x 576 dims in the K-part layout only.
+// An MLA latent page keeps the natural order: P rows of 576 dims.  Its decode kernel stages rows
+// through LDS and reads them back in both operand orders (kernels_decode_mla.hip).
 // ---------------------------------------------------------------------------------------------
 constexpr int TILE_T = 16;
 
@@ -147,6 +148,11 @@ hipError_t launch_decode_gqa(const PoolGeom& g, const char* pool_base, const voi
                              const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride,
                              int B, int H, float scale, int chunk_tiles, int max_chunks,
                              float* ws_o, float* ws_ml, hipStream_t stream);
+hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const void* q, void* out,
+                             const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride,
+                             int B, int H, float scale, int chunk_steps, int max_chunks,
+                             float* ws_o, float* ws_ml, hipStream_t stream);
+int decode_mla_step_tokens();
 hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out, const PrefillWork* d_work,
                           int n_work, int H, int Hkv, int dqk, int dv, float scale, hipStream_t stream);
 hipError_t launch_probe(int32_t* d_ids, int n_blocks, hipStream_t stream);

@@ -1,0 +1,276 @@
+// Decode step, MLA latent cache (DeepSeek-V2-style multi-head latent attention, absorbed form).
+//
+// Paper, Evaluation "Model": DeepSeek-V2-Lite / V3 are served through the same two workers; the
+// paper names the model only.  Per token the cache holds ONE latent row c_t = [ckv_t (512) ;
+// krope_t (64)] shared by all heads.  For request b and head h with absorbed query q[b,h,:576]:
+//     s[h,t]      = scale * q[b,h,:] . c_t
+//     out[b,h,:]  = sum_{t<n} softmax_t(s[h,:]) * c_t[0:512]
+// so the same bytes act as keys (contraction over the 576 dims) and as values (contraction over
+// the tokens).  34.8 kflop per 1152-byte row: the fp32 vector units cannot keep up with HBM, the
+// matrix cores must; the heads (<= 16) are the MFMA column dimension.
+//
+// One workgroup (4 waves) owns one (request, chunk of the context).  Steps of 32 tokens (36 KiB,
+// contiguous in the page: latent pages keep the natural [token][dim] order) stream
+// HBM -> LDS with global_load_lds_dwordx4 into a 4-stage ring, 3 steps (108 KiB per CU) ahead.
+// Out of LDS the rows are read twice, in the two operand orders:
+//     S^T[token, head] = C[16 x 576] . Q^T[576 x 16]      ds_read_b128     + v_mfma_f32_16x16x32_bf16
+//     O^T[dim, head]  += C^T[16 dims x 16 tokens] . P^T    ds_read_b64_tr_b16 + v_mfma_f32_16x16x16_bf16
+// Every wave computes the (small) score product and the softmax statistics redundantly and owns
+// 128 of the 512 output dims, so no cross-wave reduction is ever needed.  Split-K partials go to
+// the same workspace / combine kernel as the GQA path.
+#include "internal.h"
+
+namespace spd {
+
+typedef unsigned short bf16_t;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+namespace mla {
+constexpr int DL = 576;               // latent dims per token
+constexpr int DV = 512;               // leading dims that act as values
+constexpr int ROW_BYTES = DL * 2;     // 1152
+constexpr int CH = DL / 8;            // 72 16-byte chunks per row
+constexpr int STEP_T = 32;            // tokens per step
+constexpr int STAGE_BYTES = STEP_T * ROW_BYTES;   // 36864
+constexpr int NSTAGE = 4;
+constexpr int PD = NSTAGE - 1;
+constexpr int NI = STAGE_BYTES / 1024;            // 36 load instructions per step
+constexpr int WAVES = 4;
+constexpr int LPW = NI / WAVES;                   // 9
+constexpr int KS = DL / 32;                       // 18 k-steps of the score product
+constexpr int VB = DV / 16 / WAVES;               // 8 value blocks of 16 dims per wave
+}  // namespace mla
+
+__device__ inline uint32_t mla_pack_bf16(float a, float b) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
+}
+__device__ inline void mla_dma16(const void* gptr, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte_addr), "v"(gptr) : "memory");
+}
+#define SPD_MLA_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
+
+// grid (max_chunks, 1, B), block 256.  chunk_steps = 32-token steps per chunk.
+__global__ __launch_bounds__(256, 1) void decode_mla_kernel(
+    const char* __restrict__ pool, uint64_t page_bytes, int steps_per_page, const bf16_t* __restrict__ q,
+    bf16_t* __restrict__ out, const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ bt, int bt_stride, int H,
+    float c /* scale * log2(e) */, int chunk_steps, int max_chunks, float* __restrict__ ws_o,
+    float* __restrict__ ws_ml) {
+  using namespace mla;
+  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE_BYTES];
+  const int chunk = blockIdx.x, b = blockIdx.z;
+  const int n = ctx_lens[b];
+  const int n_steps_all = (n + STEP_T - 1) / STEP_T;
+  const int step0 = chunk * chunk_steps;
+  if (step0 >= n_steps_all) return;
+  const int n_steps = min(n_steps_all - step0, chunk_steps);
+  const int n_chunks = (n_steps_all + chunk_steps - 1) / chunk_steps;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int col = lane & 15, c4 = lane >> 4;       // col: head (B operand / accumulator column) or token (A operand row)
+  const int32_t* bt_row = bt + (size_t)b * bt_stride;
+  const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+
+  // absorbed-query fragments: B operand, column = head, dims 8 (4 s + c4) .. + 7 for k-step s
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    uint4 raw = uint4{0, 0, 0, 0};
+    if (col < H) raw = *(const uint4*)(q + ((size_t)b * H + col) * DL + 8 * (4 * s + c4));
+    qf[s] = __builtin_bit_cast(bf16x8, raw);
+  }
+
+  // ---- loads: instruction ii = wave + 4 j fills LDS slots [64 ii, 64 ii + 64) of the stage;
+  // slot s of row r holds the row's chunk s ^ (r & 7)
+  int ld_off[LPW];
+#pragma unroll
+  for (int j = 0; j < LPW; ++j) {
+    const int slot = (wave + WAVES * j) * 64 + lane, row = slot / CH, sl = slot % CH;
+    ld_off[j] = row * ROW_BYTES + ((sl ^ (row & 7)) * 16);
+  }
+  auto issue_loads = [&](int st) {            // st: step index inside the chunk
+    const int gs = step0 + st;
+    const int page = bt_row[gs / steps_per_page];
+    const char* src = pool + (uint64_t)page * page_bytes + (size_t)(gs % steps_per_page) * STAGE_BYTES;
+    const uint32_t stage = smem_base + (uint32_t)(st % NSTAGE) * STAGE_BYTES;
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) mla_dma16(src + ld_off[j], stage + (uint32_t)(wave + WAVES * j) * 1024);
+  };
+
+  // ---- LDS operand addresses (byte offsets inside a stage, for the first 16-token block)
+  // score operand (k-step s): row = col, chunk 4 s + c4  ->  slot (4 s + c4) ^ (col & 7);
+  // bit 2 of the swizzle flips the parity of s, hence two bases (even / odd s) + 128 * (s / 2)
+  const int f = (col >> 2) & 1;
+  const int k_base = col * ROW_BYTES + ((c4 ^ (col & 3)) * 16);
+  const int k_even = k_base + 64 * f, k_odd = k_base + 64 * (1 - f);
+  // value operand (16 dims of block blk): in each 16-lane group, lane r supplies row 4 c4 + r / 4
+  // and dims 4 (r % 4) .. + 3; the transpose read hands lane i dim i of those 4 tokens
+  const int v_row = 4 * c4 + (col >> 2);
+  const int v_sw = v_row & 7;
+  int v_base[4];                                   // by blk & 3; add 128 * (blk / 4) + 2048 * wave ... (below)
+#pragma unroll
+  for (int b3 = 0; b3 < 4; ++b3) {
+    const int ch_low = (2 * b3 + ((col & 3) >> 1)) ^ v_sw;         // low three bits of the chunk index
+    v_base[b3] = v_row * ROW_BYTES + (16 * wave) * 16 + ch_low * 16 + (col & 1) * 8;
+  }
+
+  f32x4 O[VB];
+#pragma unroll
+  for (int i = 0; i < VB; ++i) O[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = -INFINITY, l = 0.f;
+
+#pragma unroll
+  for (int t = 0; t < PD; ++t)
+    if (t < n_steps) issue_loads(t);
+
+  for (int st = 0; st < n_steps; ++st) {
+    const int later = min(PD - 1, n_steps - 1 - st);
+    if (later >= 2) SPD_MLA_WAIT_VMCNT(2 * LPW);
+    else if (later == 1) SPD_MLA_WAIT_VMCNT(LPW);
+    else SPD_MLA_WAIT_VMCNT(0);
+    asm volatile("s_barrier" ::: "memory");        // step st has landed for all waves; stage of st - 1 is free
+    if (st + PD < n_steps) issue_loads(st + PD);
+
+    const char* stage = smem + (st % NSTAGE) * STAGE_BYTES;
+    const int tok0 = (step0 + st) * STEP_T;         // first token of the step
+    // ---- S^T = C . Q^T for the two 16-token blocks
+    f32x4 S[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      S[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+      const char* rowp = stage + u * (16 * ROW_BYTES);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const uint4 a = *(const uint4*)(rowp + ((s & 1) ? k_odd : k_even) + 128 * (s >> 1));
+        S[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), qf[s], S[u], 0, 0, 0);
+      }
+    }
+    // lane holds, for head col, tokens tok0 + 16 u + 4 c4 + i
+    if (tok0 + STEP_T > n) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (tok0 + 16 * u + 4 * c4 + i >= n) S[u][i] = -INFINITY;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(S[0][0], S[0][1]), fmaxf(S[0][2], S[0][3])),
+                     fmaxf(fmaxf(S[1][0], S[1][1]), fmaxf(S[1][2], S[1][3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m, mx);
+    const float mc = m_new * c;
+    float psum = 0.f;
+    uint2 pb[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      float p[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        p[i] = __builtin_amdgcn_exp2f(S[u][i] * c - mc);
+        psum += p[i];
+      }
+      pb[u].x = mla_pack_bf16(p[0], p[1]);
+      pb[u].y = mla_pack_bf16(p[2], p[3]);
+    }
+    if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {        // rescale only when some running maximum moved
+      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+      l *= alpha;
+#pragma unroll
+      for (int blk = 0; blk < VB; ++blk) O[blk] *= alpha;
+      m = m_new;
+    }
+    l += psum;
+    // ---- O^T += C^T . P^T for this wave's 128 dims
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      // tokens of this lane's operand: tok0 + 16 u + 4 c4 + {0..3}; slots past the context hold arbitrary bytes
+      const int t0 = tok0 + 16 * u + 4 * c4;
+      const bool vtail = t0 + 4 > n;
+      const uint32_t m01 = (t0 + 0 < n ? 0x0000ffffu : 0u) | (t0 + 1 < n ? 0xffff0000u : 0u);
+      const uint32_t m23 = (t0 + 2 < n ? 0x0000ffffu : 0u) | (t0 + 3 < n ? 0xffff0000u : 0u);
+      const s16x4 pv = __builtin_bit_cast(s16x4, pb[u]);
+#pragma unroll
+      for (int blk = 0; blk < VB; ++blk) {
+        s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(
+            stage + u * (16 * ROW_BYTES) + v_base[blk & 3] + 128 * (blk >> 2)));
+        if (vtail) {
+          uint2 r = __builtin_bit_cast(uint2, a);
+          r.x &= m01;
+          r.y &= m23;
+          a = __builtin_bit_cast(s16x4, r);
+        }
+        O[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, pv, O[blk], 0, 0, 0);
+      }
+    }
+  }
+
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  if (col < H) {
+    const size_t head = (size_t)b * H + col;
+    if (n_chunks == 1) {
+      const float inv = 1.f / l;
+      bf16_t* op = out + head * DV + 128 * wave + 4 * c4;
+#pragma unroll
+      for (int blk = 0; blk < VB; ++blk) {
+        uint2 pk;
+        pk.x = mla_pack_bf16(O[blk][0] * inv, O[blk][1] * inv);
+        pk.y = mla_pack_bf16(O[blk][2] * inv, O[blk][3] * inv);
+        *(uint2*)(op + 16 * blk) = pk;
+      }
+    } else {
+      const size_t slot = head * max_chunks + chunk;
+      float* wp = ws_o + slot * DV + 128 * wave + 4 * c4;
+#pragma unroll
+      for (int blk = 0; blk < VB; ++blk) *(f32x4*)(wp + 16 * blk) = O[blk];
+      if (wave == 0 && c4 == 0) {
+        ws_ml[slot * 2] = m * c;
+        ws_ml[slot * 2 + 1] = l;
+      }
+    }
+  }
+}
+
+// grid (H, B), block 512: merge the chunks of one (request, head); one thread per output dim.
+__global__ __launch_bounds__(512) void decode_mla_combine_kernel(bf16_t* __restrict__ out,
+                                                                const int32_t* __restrict__ ctx_lens, int H,
+                                                                int chunk_steps, int max_chunks,
+                                                                const float* __restrict__ ws_o,
+                                                                const float* __restrict__ ws_ml) {
+  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  const int n_steps = (ctx_lens[b] + mla::STEP_T - 1) / mla::STEP_T;
+  const int n_chunks = (n_steps + chunk_steps - 1) / chunk_steps;
+  if (n_chunks <= 1) return;
+  const size_t slot0 = ((size_t)b * H + h) * max_chunks;
+  float m_tot = -INFINITY;
+  for (int ck = 0; ck < n_chunks; ++ck) m_tot = fmaxf(m_tot, ws_ml[(slot0 + ck) * 2]);
+  float l_tot = 0.f, o = 0.f;
+  for (int ck = 0; ck < n_chunks; ++ck) {
+    const float wgt = __builtin_amdgcn_exp2f(ws_ml[(slot0 + ck) * 2] - m_tot);
+    l_tot += ws_ml[(slot0 + ck) * 2 + 1] * wgt;
+    o += ws_o[(slot0 + ck) * mla::DV + d] * wgt;
+  }
+  out[((size_t)b * H + h) * mla::DV + d] = (bf16_t)(mla_pack_bf16(o / l_tot, 0.f) & 0xffffu);
+}
+
+int decode_mla_step_tokens() { return mla::STEP_T; }
+
+hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const void* q, void* out,
+                             const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride, int B, int H,
+                             float scale, int chunk_steps, int max_chunks, float* ws_o, float* ws_ml,
+                             hipStream_t stream) {
+  const float c = scale * 1.4426950408889634f;
+  hipLaunchKernelGGL(decode_mla_kernel, dim3(max_chunks, 1, B), dim3(256), 0, stream, pool_base, g.page_bytes,
+                     g.P / mla::STEP_T, (const bf16_t*)q, (bf16_t*)out, d_ctx_lens, d_block_tables, bt_stride, H, c,
+                     chunk_steps, max_chunks, ws_o, ws_ml);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || max_chunks <= 1) return e;
+  hipLaunchKernelGGL(decode_mla_combine_kernel, dim3(H, B), dim3(512), 0, stream, (bf16_t*)out, d_ctx_lens, H,
+                     chunk_steps, max_chunks, ws_o, ws_ml);
+  return hipGetLastError();
+}
+
+}  // namespace spd

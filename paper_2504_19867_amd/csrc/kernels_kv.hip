@@ -16,17 +16,19 @@ __global__ __launch_bounds__(256) void kv_write_kernel(char* __restrict__ base, 
                                                        uint32_t head_bytes, uint32_t tile_bytes,
                                                        uint32_t tile_k_bytes, const TileDesc* __restrict__ descs,
                                                        const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-                                                       int Hkv, int dk, int dv) {
+                                                       int Hkv, int dk, int dv, int natural) {
   const TileDesc d = descs[blockIdx.x];
   const int g = blockIdx.y;
   char* tile = base + (uint64_t)d.page * page_bytes + (uint64_t)g * head_bytes + (uint64_t)d.sub * tile_bytes;
-  // K part: [chunk][token][8 dims], one 16-byte piece per (chunk, token)
+  // K part: [chunk][token][8 dims] (GQA) or natural [token][dim] rows (MLA latent), one 16-byte
+  // piece per (chunk, token)
   const int k_items = (dk >> 3) * TILE_T;
   for (int i = threadIdx.x; i < k_items; i += blockDim.x) {
     const int t = i & 15, c = i >> 4;
     if (t >= d.t_begin && t < d.t_end) {
       const bf16_t* src = k + ((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dk + c * 8;
-      *(uint4*)(tile + ((size_t)(c * 16 + t) << 4)) = *(const uint4*)src;
+      const size_t off = natural ? (size_t)t * dk * 2 + (size_t)c * 16 : ((size_t)(c * 16 + t) << 4);
+      *(uint4*)(tile + off) = *(const uint4*)src;
     }
   }
   if (v == nullptr) return;
@@ -69,7 +71,7 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(const char* __restrict__
                                                         uint32_t head_bytes, uint32_t tile_bytes,
                                                         uint32_t tile_k_bytes, const TileDesc* __restrict__ descs,
                                                         bf16_t* __restrict__ k_out, bf16_t* __restrict__ v_out,
-                                                        int Hkv, int dk, int dv) {
+                                                        int Hkv, int dk, int dv, int natural) {
   const TileDesc d = descs[blockIdx.x];
   const int g = blockIdx.y;
   const char* tile = base + (uint64_t)d.page * page_bytes + (uint64_t)g * head_bytes + (uint64_t)d.sub * tile_bytes;
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(const char* __restrict__
   const int nt = d.t_end - d.t_begin;
   for (int i = threadIdx.x; i < nt * dk; i += blockDim.x) {
     const int t = d.t_begin + i / dk, dd = i % dk;
-    k_out[((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dk + dd] = kt[k_elem_offset(t, dd)];
+    k_out[((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dk + dd] = kt[natural ? (uint32_t)(t * dk + dd) : k_elem_offset(t, dd)];
   }
   if (v_out == nullptr) return;
   for (int i = threadIdx.x; i < nt * dv; i += blockDim.x) {
@@ -117,7 +119,8 @@ hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d
                            const void* v, hipStream_t stream) {
   if (n_tiles <= 0) return hipSuccess;
   hipLaunchKernelGGL(kv_write_kernel, dim3(n_tiles, g.Hkv), dim3(256), 0, stream, pool_base, g.page_bytes, g.head_bytes,
-                     g.tile_bytes, g.tile_k_bytes, d_tiles, (const bf16_t*)k, (const bf16_t*)v, g.Hkv, g.dk, g.dv);
+                     g.tile_bytes, g.tile_k_bytes, d_tiles, (const bf16_t*)k, (const bf16_t*)v, g.Hkv, g.dk, g.dv,
+                     g.kind == SPD_KV_MLA_LATENT ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -126,7 +129,7 @@ hipError_t launch_kv_gather(const PoolGeom& g, const char* pool_base, const Tile
   if (n_tiles <= 0) return hipSuccess;
   hipLaunchKernelGGL(kv_gather_kernel, dim3(n_tiles, g.Hkv), dim3(256), 0, stream, pool_base, g.page_bytes,
                      g.head_bytes, g.tile_bytes, g.tile_k_bytes, d_tiles, (bf16_t*)k_out, (bf16_t*)v_out, g.Hkv, g.dk,
-                     g.dv);
+                     g.dv, g.kind == SPD_KV_MLA_LATENT ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -145,15 +145,18 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
 }
 
 // ------------------------------------------------------------------------------------------ decode
-static int decode_chunk_tiles(int64_t sum_tiles, int Hkv, int cus) {
+// Split-K chunk length in units (16-token tiles for GQA, 32-token steps for MLA).
+static int decode_chunk_units(int64_t sum_units, int Hkv, int cus, bool mla) {
   static const char* env = getenv("SPD_DECODE_CHUNK_TILES");
-  if (env && atoi(env) > 0) return (atoi(env) + 7) / 8 * 8;
-  // aim at ~8 workgroups per CU of the decode share so that unequal contexts balance out
-  int64_t target_wgs = (int64_t)cus * 8;
+  const int64_t round = mla ? 1 : 8;              // GQA: 4 waves x 2 tiles per step
+  if (env && atoi(env) > 0) return (int)((atoi(env) + round - 1) / round * round);
+  // aim at ~8 (GQA, two workgroups per CU) or ~4 (MLA, one per CU) workgroups per CU of the decode
+  // share so that unequal contexts balance out
+  int64_t target_wgs = (int64_t)cus * (mla ? 4 : 8);
   int64_t per_head_chunks = std::max<int64_t>(1, target_wgs / std::max(1, Hkv));
-  int64_t c = (sum_tiles + per_head_chunks - 1) / per_head_chunks;
-  c = (c + 7) / 8 * 8;
-  return (int)std::min<int64_t>(std::max<int64_t>(c, 16), 1 << 20);
+  int64_t c = (sum_units + per_head_chunks - 1) / per_head_chunks;
+  c = (c + round - 1) / round * round;
+  return (int)std::min<int64_t>(std::max<int64_t>(c, mla ? 8 : 16), 1 << 20);
 }
 
 extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* b) {
@@ -172,13 +175,14 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
         if (b->req_ids[r2] == b->req_ids[r]) return SPD_EINVAL;
   }
   if (ctx->device < 0) return SPD_ESTATE;
-  if (g.kind != SPD_KV_GQA) return SPD_ESTATE;   // MLA-latent decode kernel: see kernels_decode_mla.hip
 
   const int B = b->n_req;
+  const bool mla = g.kind == SPD_KV_MLA_LATENT;
+  const int unit_t = mla ? decode_mla_step_tokens() : TILE_T;     // tokens per split-K unit
   int64_t sum_tiles = 0;
   int32_t max_tiles = 0, max_pages = 0;
   for (int r = 0; r < B; ++r) {
-    int32_t tiles = (b->ctx_lens[r] + TILE_T - 1) / TILE_T;
+    int32_t tiles = (b->ctx_lens[r] + unit_t - 1) / unit_t;
     sum_tiles += tiles;
     max_tiles = std::max(max_tiles, tiles);
     max_pages = std::max(max_pages, (b->ctx_lens[r] + g.P - 1) / g.P);
@@ -189,7 +193,7 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
   int rc = phase_enter(ctx, SPD_PHASE_DECODE, &stream);
   if (rc != SPD_OK) return rc;
   spd_phase_state& ds = ctx->phase[SPD_PHASE_DECODE];
-  const int chunk_tiles = decode_chunk_tiles(sum_tiles, g.Hkv, ds.active_cus);
+  const int chunk_tiles = decode_chunk_units(sum_tiles, g.Hkv, ds.active_cus, mla);
   const int max_chunks = (max_tiles + chunk_tiles - 1) / chunk_tiles;
 
   size_t off_bt = align16(sizeof(int32_t) * (size_t)B);
@@ -238,9 +242,14 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
   if (append)
     SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(st->dev + off_desc), B, b->k_new, b->v_new, stream));
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 0, stream)) != SPD_OK) return rc;
-  SPD_HIP(launch_decode_gqa(g, pool->base, b->q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
-                            bt_stride, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks, (float*)ws,
-                            (float*)(ws ? ws + ws_o_bytes : nullptr), stream));
+  if (mla)
+    SPD_HIP(launch_decode_mla(g, pool->base, b->q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
+                              bt_stride, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks, (float*)ws,
+                              (float*)(ws ? ws + ws_o_bytes : nullptr), stream));
+  else
+    SPD_HIP(launch_decode_gqa(g, pool->base, b->q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
+                              bt_stride, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks, (float*)ws,
+                              (float*)(ws ? ws + ws_o_bytes : nullptr), stream));
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 1, stream)) != SPD_OK) return rc;
   SPD_HIP(hipEventRecord(ds.ev_end, stream));
   ds.timed = true;
