@@ -34,6 +34,7 @@ def parse():
     ap.add_argument("--no-sweep", action="store_true", help="skip the CU-split sweep (solo + concurrent per split)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--pool-gb", type=float, default=None, help="override pool size (GB)")
+    ap.add_argument("--no-scramble", action="store_true", help="experiment: hand out physical pages in order")
     ap.add_argument("--only", default=None, choices=[None, "prefill", "decode"],
                     help="profiling aid: run only one phase in the timed region")
     return ap.parse_args()
@@ -45,7 +46,7 @@ def median(xs):
 
 
 class Bench:
-    def __init__(self, cfg, pool_gb=None):
+    def __init__(self, cfg, pool_gb=None, scramble=True):
         import torch
         from paper_2504_19867_amd import semipd as S
         self.torch, self.S, self.cfg = torch, S, cfg
@@ -56,21 +57,24 @@ class Bench:
         self.total_cus, self.xcds, self.gran = self.ctx.device_info()
         num_pages = cfg.num_pages if pool_gb is None else int(pool_gb * 1e9) // L.page_bytes
         self.num_pages = num_pages
-        nbytes = S.pool_bytes(S.SPD_KV_GQA, L.page_tokens, L.n_kv_heads, L.dim_qk, L.dim_v, num_pages)
+        mla = L.kind == "mla"
+        kind = S.SPD_KV_MLA_LATENT if mla else S.SPD_KV_GQA
+        pk, pv = (L.latent_dim, L.latent_v_dim) if mla else (L.dim_qk, L.dim_v)
+        nbytes = S.pool_bytes(kind, L.page_tokens, L.n_kv_heads, pk, pv, num_pages)
         self.mem = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
-        self.pool = S.Pool(self.ctx, self.mem, nbytes, S.SPD_KV_GQA, L.page_tokens, L.n_kv_heads, L.dim_qk, L.dim_v,
-                           num_pages)
+        self.pool = S.Pool(self.ctx, self.mem, nbytes, kind, L.page_tokens, L.n_kv_heads, pk, pv, num_pages)
         self.scale = 1.0 / math.sqrt(L.dim_qk)
         gen = torch.Generator(device=self.dev)
         gen.manual_seed(cfg.seed)
 
-        def randn(*shape):
-            return torch.randn(*shape, generator=gen, device=self.dev, dtype=torch.float32).to(torch.bfloat16)
+        def randn(*shape, std=1.0):
+            x = torch.randn(*shape, generator=gen, device=self.dev, dtype=torch.float32)
+            return (x * std if std != 1.0 else x).to(torch.bfloat16)
 
         # scattered physical pages, as after long serving
         import workloads as W
         touched = min(num_pages - 8, 4 * sum(-(-n // L.page_tokens) for n in cfg.decode_ctx) * 3)
-        for op, r, n in W.scramble_ops(touched, L.page_tokens, cfg.seed):
+        for op, r, n in (W.scramble_ops(touched, L.page_tokens, cfg.seed) if scramble else []):
             self.pool.kv_reserve(r, n) if op == "reserve" else self.pool.kv_free(r)
 
         # decode: 3 disjoint request sets (> 256 MB apart in use) so that no step finds its KV in cache
@@ -81,12 +85,20 @@ class Bench:
             ids = [10_000 * (s + 1) + i for i in range(self.B)]
             for rid, n in zip(ids, cfg.decode_ctx):
                 self.pool.kv_reserve(rid, n)
-                k = randn(n, L.n_kv_heads, L.dim_qk)
-                v = randn(n, L.n_kv_heads, L.dim_v)
-                self.pool.kv_write(DEC, rid, 0, n, k, v)
+                if mla:
+                    self.pool.kv_write(DEC, rid, 0, n, randn(n, L.latent_dim))
+                else:
+                    k = randn(n, L.n_kv_heads, L.dim_qk)
+                    v = randn(n, L.n_kv_heads, L.dim_v)
+                    self.pool.kv_write(DEC, rid, 0, n, k, v)
             self.ctx.phase_sync(DEC)
-            q = randn(self.B, L.n_q_heads, L.dim_qk)
-            out = torch.empty((self.B, L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=self.dev)
+            if mla:
+                q = randn(self.B, L.n_q_heads, L.latent_dim)
+                q[..., : L.latent_v_dim] *= float(W.MLA_QABS_NOPE_STD)
+                out = torch.empty((self.B, L.n_q_heads, L.latent_v_dim), dtype=torch.bfloat16, device=self.dev)
+            else:
+                q = randn(self.B, L.n_q_heads, L.dim_qk)
+                out = torch.empty((self.B, L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=self.dev)
             self.dec_batches.append(self.pool.make_decode_batch(ids, cfg.decode_ctx, q, out, L.n_q_heads, self.scale))
         # prefill: 2 input sets
         self.T = sum(cfg.prefill_lens)
@@ -94,20 +106,26 @@ class Bench:
         for n in cfg.prefill_lens:
             cu.append(cu[-1] + n)
         self.pre_batches = []
+        kvh = L.n_q_heads if mla else L.n_kv_heads          # MLA prefill is the un-absorbed multi-head form
         for s in range(2):
             q = randn(self.T, L.n_q_heads, L.dim_qk)
-            k = randn(self.T, L.n_kv_heads, L.dim_qk)
-            v = randn(self.T, L.n_kv_heads, L.dim_v)
+            k = randn(self.T, kvh, L.dim_qk, std=float(W.MLA_UP_STD) if mla else 1.0)
+            v = randn(self.T, kvh, L.dim_v, std=float(W.MLA_UP_STD) if mla else 1.0)
+            latent = randn(self.T, L.latent_dim) if mla else None
             out = torch.empty((self.T, L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=self.dev)
             ids = [100 * (s + 1) + i for i in range(len(cfg.prefill_lens))]
-            self.pre_batches.append(self.pool.make_prefill_batch(ids, cu, q, k, v, out, L.n_q_heads, L.n_kv_heads,
-                                                                 L.dim_qk, L.dim_v, self.scale))
+            self.pre_batches.append(self.pool.make_prefill_batch(ids, cu, q, k, v, out, L.n_q_heads, kvh,
+                                                                 L.dim_qk, L.dim_v, self.scale, latent=latent))
         torch.cuda.synchronize()
         # algorithmic work
         G = L.n_q_heads
         self.prefill_flops = sum(2.0 * (L.dim_qk + L.dim_v) * G * n * (n + 1) / 2 for n in cfg.prefill_lens)
-        kv_bytes = sum(cfg.decode_ctx) * L.n_kv_heads * (L.dim_qk + L.dim_v) * 2
-        qo_bytes = self.B * L.n_q_heads * (L.dim_qk + L.dim_v) * 2
+        if mla:
+            kv_bytes = sum(cfg.decode_ctx) * L.latent_dim * 2
+            qo_bytes = self.B * L.n_q_heads * (L.latent_dim + L.latent_v_dim) * 2
+        else:
+            kv_bytes = sum(cfg.decode_ctx) * L.n_kv_heads * (L.dim_qk + L.dim_v) * 2
+            qo_bytes = self.B * L.n_q_heads * (L.dim_qk + L.dim_v) * 2
         self.decode_bytes = float(kv_bytes + qo_bytes)
         self.n_pre = self.n_dec = 0
 
@@ -128,24 +146,47 @@ class Bench:
         self.prefill(); self.decode(); self.sync()          # both phases adopt the new streams
         return self.ctx.get_partition()[:2]
 
+    def copy_ceiling(self, phase, nbytes=1 << 30, reps=3):
+        """GB/s (read + write bytes) of a plain copy kernel on the phase's stream: streaming ceiling of its CU share"""
+        torch = self.torch
+        if not hasattr(self, "_cp"):
+            self._cp = (torch.empty(nbytes, dtype=torch.uint8, device=self.dev),
+                        torch.empty(nbytes, dtype=torch.uint8, device=self.dev))
+        a, b = self._cp
+        self.ctx.phase_copy(phase, b, a, nbytes)
+        self.ctx.phase_sync(phase)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            self.ctx.phase_copy(phase, b, a, nbytes)
+        self.ctx.phase_sync(phase)
+        return 2.0 * nbytes * reps / (time.perf_counter() - t0) / 1e9
+
     def time_solo(self, phase, n):
         """median kernel-level and step-level ms of `n` back-to-back steps of one phase, other phase idle"""
         fn = self.prefill if phase == PRE else self.decode
+        self.ctx.set_kernel_timing(False)
         for _ in range(3):
             fn()
         self.ctx.phase_sync(phase)
-        self.ctx.phase_kernel_ms(phase)
         t0 = time.perf_counter()
         for _ in range(n):
             fn()
         self.ctx.phase_sync(phase)
         wall = (time.perf_counter() - t0) * 1e3 / n
-        return median(self.ctx.phase_kernel_ms(phase)), wall
+        self.ctx.set_kernel_timing(True)
+        self.ctx.phase_kernel_ms(phase)
+        for _ in range(n):
+            fn()
+        kms = self.ctx.phase_kernel_ms(phase)
+        self.ctx.set_kernel_timing(False)
+        return median(kms), wall
 
-    def run_concurrent(self, steps, r, only=None):
-        """`steps` steps of (1 prefill || r decodes); returns wall ms/step and per-phase kernel ms lists"""
+    def run_concurrent(self, steps, r, only=None, timing=False):
+        """`steps` steps of (1 prefill || r decodes); returns wall ms/step and per-phase kernel ms lists
+        (the lists are empty unless `timing`: event records slow the pipeline, so the throughput pass runs without)"""
         torch = self.torch
         self.sync()
+        self.ctx.set_kernel_timing(timing)
         self.ctx.phase_kernel_ms(PRE); self.ctx.phase_kernel_ms(DEC)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -158,7 +199,9 @@ class Bench:
         self.sync()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-        return wall_ms, self.ctx.phase_kernel_ms(PRE), self.ctx.phase_kernel_ms(DEC)
+        pk, dk = self.ctx.phase_kernel_ms(PRE), self.ctx.phase_kernel_ms(DEC)
+        self.ctx.set_kernel_timing(False)
+        return wall_ms, pk, dk
 
 
 def cpu_baseline(cfg, r):
@@ -169,19 +212,29 @@ def cpu_baseline(cfg, r):
     L = cfg.layer
     scale = 1.0 / math.sqrt(L.dim_qk)
     G = L.n_q_heads // L.n_kv_heads
+    f = lambda b: W.bf16_bits_to_f32(b).astype(np.float64)
+    mla = L.kind == "mla"
     # prefill sample: request 0, all heads
     n0 = cfg.prefill_lens[0]
-    q, k, v, cu = W.prefill_inputs(L, (n0,), cfg.seed)
-    f = lambda b: W.bf16_bits_to_f32(b).astype(np.float64)
+    if mla:
+        q, k, v, _, cu = W.mla_prefill_inputs(L, (n0,), cfg.seed)
+    else:
+        q, k, v, cu = W.prefill_inputs(L, (n0,), cfg.seed)
     t0 = time.perf_counter()
     OA.prefill_attention(f(q), f(k), f(v), cu, scale)
     t_p = (time.perf_counter() - t0) * (sum(cfg.prefill_lens) / n0)                   # whole prefill batch
-    # decode sample: first half of the requests, all heads
-    ns = cfg.decode_ctx[: max(1, len(cfg.decode_ctx) // 2)]
-    qd, ks, vs = W.decode_inputs(L, ns, cfg.seed + 1)
-    t0 = time.perf_counter()
-    for i in range(len(ns)):
-        OA.decode_attention(f(qd[i]), f(ks[i]), f(vs[i]), scale)
+    # decode sample: first quarter (MLA) or half (GQA) of the requests, all heads
+    ns = cfg.decode_ctx[: max(1, len(cfg.decode_ctx) // (4 if mla else 2))]
+    if mla:
+        qd, cs = W.mla_decode_inputs(L, ns, cfg.seed + 1)
+        t0 = time.perf_counter()
+        for i in range(len(ns)):
+            OA.mla_decode_latent(f(qd[i]), f(cs[i]), scale, L.latent_v_dim)
+    else:
+        qd, ks, vs = W.decode_inputs(L, ns, cfg.seed + 1)
+        t0 = time.perf_counter()
+        for i in range(len(ns)):
+            OA.decode_attention(f(qd[i]), f(ks[i]), f(vs[i]), scale)
     t_d = (time.perf_counter() - t0) * (sum(cfg.decode_ctx) / sum(ns))                # whole decode batch
     try:
         from threadpoolctl import threadpool_info
@@ -204,19 +257,20 @@ def main():
         sys.exit(2)
     import workloads as W
     cfg = W.get_config(args.config)
-    bench = Bench(cfg, args.pool_gb)
-    bench.ctx.set_kernel_timing(True)
+    bench = Bench(cfg, args.pool_gb, not args.no_scramble)
     p_pct, d_pct = (int(x) for x in args.split.split("/"))
 
     def measure_split(pp, dp, steps, warmup, only=None):
         p_cus, d_cus = bench.set_split(pp, dp)
+        copy_gbs = bench.copy_ceiling(DEC)
         solo_p_k, solo_p_w = bench.time_solo(PRE, max(5, steps // 4))
         solo_d_k, solo_d_w = bench.time_solo(DEC, max(10, steps))
         r = max(1, round(solo_p_w / solo_d_w))
         bench.run_concurrent(warmup, r, only)
-        wall_ms, pk, dk = bench.run_concurrent(steps, r, only)
+        wall_ms, _, _ = bench.run_concurrent(steps, r, only)                       # the timed region: K steps
+        _, pk, dk = bench.run_concurrent(min(steps, 64), r, only, timing=True)     # same steps again, kernels bracketed by events
         return {"split": f"{pp}/{dp}", "prefill_cus": p_cus, "decode_cus": d_cus, "decode_per_prefill": r,
-                "ms_per_step": wall_ms,
+                "ms_per_step": wall_ms, "decode_share_copy_gbs": copy_gbs,
                 "prefill_tok_s": bench.T / wall_ms * 1e3 if only != "decode" else 0.0,
                 "decode_tok_s": r * bench.B / wall_ms * 1e3 if only != "prefill" else 0.0,
                 "prefill_kernel_ms": median(pk), "decode_kernel_ms": median(dk),
@@ -250,13 +304,13 @@ def main():
                    "cu_split": head["split"], "prefill_cus": head["prefill_cus"], "decode_cus": head["decode_cus"],
                    "step": f"1 prefill step || {r} decode steps", "only": args.only},
         "prefill_tok_s": head["prefill_tok_s"], "decode_tok_s": head["decode_tok_s"],
-        "roofline": {"bound": "mfma", "kernel": "prefill_kernel<128,128>", "achieved": head["prefill_tflops"],
+        "roofline": {"bound": "mfma", "kernel": f"prefill_kernel<{cfg.layer.dim_qk},{cfg.layer.dim_v}>", "achieved": head["prefill_tflops"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": (head["prefill_tflops"] or 0.0) / PEAK_BF16_TFLOPS, "traffic": None,
                      "kernel_ms": pre_ms, "flops_per_launch": bench.prefill_flops,
                      "share_cus": head["prefill_cus"],
                      "frac_of_share_peak": (head["prefill_tflops"] or 0.0) / (PEAK_BF16_TFLOPS * head["prefill_cus"] / bench.total_cus)},
-        "roofline_decode": {"bound": "hbm", "kernel": "decode_gqa_kernel<128> (+combine)", "achieved": head["decode_gbs"],
+        "roofline_decode": {"bound": "hbm", "kernel": ("decode_mla_kernel" if cfg.layer.kind == "mla" else f"decode_gqa_kernel<{cfg.layer.dim_qk}>") + " (+combine)", "achieved": head["decode_gbs"],
                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": (head["decode_gbs"] or 0.0) / PEAK_HBM_GBS,
                             "traffic": None, "kernel_ms": head["decode_kernel_ms"],
                             "bytes_per_launch": bench.decode_bytes, "share_cus": head["decode_cus"]},

@@ -190,10 +190,12 @@ int spd_phase_query(spd_ctx* ctx, int phase, int* done);
 int spd_phase_wait_for(spd_ctx* ctx, int phase, int other);
 /* The phase's current hipStream_t, for callers that enqueue their own work or events. */
 int spd_phase_stream(spd_ctx* ctx, int phase, void** hip_stream_out);
-/* GPU time of the phase's most recent step in milliseconds (waits for that step). */
+/* GPU time of the phase's most recent step in milliseconds (waits for that step).  Steps are
+ * timed only while timing is on (spd_set_kernel_timing); otherwise SPD_ESTATE. */
 int spd_phase_last_ms(spd_ctx* ctx, int phase, float* ms);
 
-/* Measurement aid.  With kernel timing on, each step brackets its attention kernel(s) (not the
+/* Measurement aid.  With timing on, each step is bracketed by HIP events (spd_phase_last_ms)
+ * and, separately, so are its attention kernel(s) (not the
  * block-table upload or the page write) with HIP events on the phase's stream; the last
  * 256 steps are kept.  spd_phase_kernel_ms waits for the phase, writes the durations
  * (milliseconds, oldest first) of the steps recorded since the last call to host out[cap]

@@ -146,12 +146,12 @@ hipError_t launch_kv_gather(const PoolGeom& g, const char* pool_base, const Tile
                             void* k_out, void* v_out, hipStream_t stream);
 hipError_t launch_decode_gqa(const PoolGeom& g, const char* pool_base, const void* q, void* out,
                              const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride,
-                             int B, int H, float scale, int chunk_tiles, int max_chunks,
-                             float* ws_o, float* ws_ml, hipStream_t stream);
+                             const void* d_items, int n_items, int B, int H, float scale, int chunk_tiles,
+                             int max_chunks, float* ws_o, float* ws_ml, hipStream_t stream);
 hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const void* q, void* out,
                              const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride,
-                             int B, int H, float scale, int chunk_steps, int max_chunks,
-                             float* ws_o, float* ws_ml, hipStream_t stream);
+                             const void* d_items, int n_items, int B, int H, float scale, int chunk_steps,
+                             int max_chunks, float* ws_o, float* ws_ml, hipStream_t stream);
 int decode_mla_step_tokens();
 hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out, const PrefillWork* d_work,
                           int n_work, int H, int Hkv, int dqk, int dv, float scale, hipStream_t stream);

@@ -127,14 +127,18 @@ __device__ inline void compute_step(const TileFrag<D>& f, const bf16x8 (&qf)[D /
   }
 }
 
-// grid (max_chunks, n_kv_heads, B), block 256
+// grid (n_items * n_kv_heads), block 256; workgroup i serves KV head i % n_kv_heads of work item
+// i / n_kv_heads = (request, chunk).  Heads vary fastest so that the round-robin placement of
+// workgroups on the 8 XCDs gives every XCD the same mix of long and short chunks.
 template <int D>
 __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(
     const char* __restrict__ pool, uint64_t page_bytes, uint32_t head_bytes, uint32_t tile_bytes, int tiles_per_page,
     const bf16_t* __restrict__ q, bf16_t* __restrict__ out, const int32_t* __restrict__ ctx_lens,
-    const int32_t* __restrict__ bt, int bt_stride, int H, int G, float c /* scale * log2(e) */, int chunk_tiles,
-    int max_chunks, float* __restrict__ ws_o, float* __restrict__ ws_ml) {
-  const int chunk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int32_t* __restrict__ bt, int bt_stride, const int2* __restrict__ items, int Hkv, int H, int G,
+    float c /* scale * log2(e) */, int chunk_tiles, int max_chunks, float* __restrict__ ws_o,
+    float* __restrict__ ws_ml) {
+  const int2 item = items[blockIdx.x / Hkv];
+  const int b = item.x, chunk = item.y, g = blockIdx.x % Hkv;
   const int n = ctx_lens[b];
   const int n_tiles = (n + TILE_T - 1) / TILE_T;
   const int tile0 = chunk * chunk_tiles;
@@ -243,13 +247,13 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(bf16_t* __restrict__ 
 
 template <int D>
 static hipError_t launch_decode_gqa_t(const PoolGeom& g, const char* pool_base, const void* q, void* out,
-                                      const int32_t* d_ctx_lens, const int32_t* d_bt, int bt_stride, int B, int H,
-                                      float scale, int chunk_tiles, int max_chunks, float* ws_o, float* ws_ml,
-                                      hipStream_t stream) {
+                                      const int32_t* d_ctx_lens, const int32_t* d_bt, int bt_stride,
+                                      const int2* d_items, int n_items, int B, int H, float scale, int chunk_tiles,
+                                      int max_chunks, float* ws_o, float* ws_ml, hipStream_t stream) {
   const float c = scale * 1.4426950408889634f;
-  hipLaunchKernelGGL(decode_gqa_kernel<D>, dim3(max_chunks, g.Hkv, B), dim3(256), 0, stream, pool_base, g.page_bytes,
-                     g.head_bytes, g.tile_bytes, g.tiles_per_page, (const bf16_t*)q, (bf16_t*)out, d_ctx_lens, d_bt,
-                     bt_stride, H, H / g.Hkv, c, chunk_tiles, max_chunks, ws_o, ws_ml);
+  hipLaunchKernelGGL(decode_gqa_kernel<D>, dim3((unsigned)n_items * g.Hkv), dim3(256), 0, stream, pool_base,
+                     g.page_bytes, g.head_bytes, g.tile_bytes, g.tiles_per_page, (const bf16_t*)q, (bf16_t*)out, d_ctx_lens,
+                     d_bt, bt_stride, d_items, g.Hkv, H, H / g.Hkv, c, chunk_tiles, max_chunks, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || max_chunks <= 1) return e;
   hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(H, B), dim3(D), 0, stream, (bf16_t*)out, d_ctx_lens, H, chunk_tiles,
@@ -258,15 +262,15 @@ static hipError_t launch_decode_gqa_t(const PoolGeom& g, const char* pool_base, 
 }
 
 hipError_t launch_decode_gqa(const PoolGeom& g, const char* pool_base, const void* q, void* out,
-                             const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride, int B, int H,
-                             float scale, int chunk_tiles, int max_chunks, float* ws_o, float* ws_ml,
-                             hipStream_t stream) {
+                             const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride,
+                             const void* d_items, int n_items, int B, int H, float scale, int chunk_tiles,
+                             int max_chunks, float* ws_o, float* ws_ml, hipStream_t stream) {
   if (g.dk == 128)
-    return launch_decode_gqa_t<128>(g, pool_base, q, out, d_ctx_lens, d_block_tables, bt_stride, B, H, scale,
-                                    chunk_tiles, max_chunks, ws_o, ws_ml, stream);
+    return launch_decode_gqa_t<128>(g, pool_base, q, out, d_ctx_lens, d_block_tables, bt_stride, (const int2*)d_items,
+                                    n_items, B, H, scale, chunk_tiles, max_chunks, ws_o, ws_ml, stream);
   if (g.dk == 64)
-    return launch_decode_gqa_t<64>(g, pool_base, q, out, d_ctx_lens, d_block_tables, bt_stride, B, H, scale,
-                                   chunk_tiles, max_chunks, ws_o, ws_ml, stream);
+    return launch_decode_gqa_t<64>(g, pool_base, q, out, d_ctx_lens, d_block_tables, bt_stride, (const int2*)d_items,
+                                   n_items, B, H, scale, chunk_tiles, max_chunks, ws_o, ws_ml, stream);
   return hipErrorInvalidValue;
 }
 

@@ -53,15 +53,16 @@ __device__ inline void mla_dma16(const void* gptr, uint32_t lds_byte_addr) {
 }
 #define SPD_MLA_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
 
-// grid (max_chunks, 1, B), block 256.  chunk_steps = 32-token steps per chunk.
+// grid (n_items), block 256: work item = (request, chunk).  chunk_steps = 32-token steps per chunk.
 __global__ __launch_bounds__(256, 1) void decode_mla_kernel(
     const char* __restrict__ pool, uint64_t page_bytes, int steps_per_page, const bf16_t* __restrict__ q,
-    bf16_t* __restrict__ out, const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ bt, int bt_stride, int H,
-    float c /* scale * log2(e) */, int chunk_steps, int max_chunks, float* __restrict__ ws_o,
+    bf16_t* __restrict__ out, const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ bt, int bt_stride,
+    const int2* __restrict__ items, int H, float c /* scale * log2(e) */, int chunk_steps, int max_chunks, float* __restrict__ ws_o,
     float* __restrict__ ws_ml) {
   using namespace mla;
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE_BYTES];
-  const int chunk = blockIdx.x, b = blockIdx.z;
+  const int2 item = items[blockIdx.x];
+  const int b = item.x, chunk = item.y;
   const int n = ctx_lens[b];
   const int n_steps_all = (n + STEP_T - 1) / STEP_T;
   const int step0 = chunk * chunk_steps;
@@ -259,13 +260,13 @@ __global__ __launch_bounds__(512) void decode_mla_combine_kernel(bf16_t* __restr
 int decode_mla_step_tokens() { return mla::STEP_T; }
 
 hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const void* q, void* out,
-                             const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride, int B, int H,
-                             float scale, int chunk_steps, int max_chunks, float* ws_o, float* ws_ml,
-                             hipStream_t stream) {
+                             const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride,
+                             const void* d_items, int n_items, int B, int H, float scale, int chunk_steps,
+                             int max_chunks, float* ws_o, float* ws_ml, hipStream_t stream) {
   const float c = scale * 1.4426950408889634f;
-  hipLaunchKernelGGL(decode_mla_kernel, dim3(max_chunks, 1, B), dim3(256), 0, stream, pool_base, g.page_bytes,
-                     g.P / mla::STEP_T, (const bf16_t*)q, (bf16_t*)out, d_ctx_lens, d_block_tables, bt_stride, H, c,
-                     chunk_steps, max_chunks, ws_o, ws_ml);
+  hipLaunchKernelGGL(decode_mla_kernel, dim3((unsigned)n_items), dim3(256), 0, stream, pool_base, g.page_bytes,
+                     g.P / mla::STEP_T, (const bf16_t*)q, (bf16_t*)out, d_ctx_lens, d_block_tables, bt_stride,
+                     (const int2*)d_items, H, c, chunk_steps, max_chunks, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || max_chunks <= 1) return e;
   hipLaunchKernelGGL(decode_mla_combine_kernel, dim3(H, B), dim3(512), 0, stream, (bf16_t*)out, d_ctx_lens, H,

@@ -129,7 +129,7 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   memcpy(st->host, work.data(), work.size() * sizeof(PrefillWork));
   memcpy(st->host + off_desc, descs.data(), descs.size() * sizeof(TileDesc));
   spd_phase_state& ps = ctx->phase[SPD_PHASE_PREFILL];
-  SPD_HIP(hipEventRecord(ps.ev_start, stream));
+  if (ctx->kernel_timing) SPD_HIP(hipEventRecord(ps.ev_start, stream));
   if ((rc = stage_commit(ctx, SPD_PHASE_PREFILL, st, bytes, stream)) != SPD_OK) return rc;
   const void* page_src_k = g.kind == SPD_KV_GQA ? b->k : b->latent;
   const void* page_src_v = g.kind == SPD_KV_GQA ? b->v : nullptr;
@@ -139,20 +139,23 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   SPD_HIP(launch_prefill(b->q, b->k, b->v, b->out, (const PrefillWork*)st->dev, (int)work.size(), b->n_q_heads,
                          b->n_kv_heads, b->dim_qk, b->dim_v, b->scale, stream));
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_PREFILL, 1, stream)) != SPD_OK) return rc;
-  SPD_HIP(hipEventRecord(ps.ev_end, stream));
-  ps.timed = true;
+  if (ctx->kernel_timing) {
+    SPD_HIP(hipEventRecord(ps.ev_end, stream));
+    ps.timed = true;
+  }
   return SPD_OK;
 }
 
 // ------------------------------------------------------------------------------------------ decode
 // Split-K chunk length in units (16-token tiles for GQA, 32-token steps for MLA).
 static int decode_chunk_units(int64_t sum_units, int Hkv, int cus, bool mla) {
-  static const char* env = getenv("SPD_DECODE_CHUNK_TILES");
+  const char* env = getenv("SPD_DECODE_CHUNK_TILES");   // tuning override, read per call
   const int64_t round = mla ? 1 : 8;              // GQA: 4 waves x 2 tiles per step
   if (env && atoi(env) > 0) return (int)((atoi(env) + round - 1) / round * round);
-  // aim at ~8 (GQA, two workgroups per CU) or ~4 (MLA, one per CU) workgroups per CU of the decode
-  // share so that unequal contexts balance out
-  int64_t target_wgs = (int64_t)cus * (mla ? 4 : 8);
+  // aim at ~6 (GQA, two workgroups per CU) or ~4 (MLA, one per CU) workgroups per CU of the decode
+  // share: enough to balance unequal contexts (items are issued longest first), few enough to keep
+  // the split-K partials small
+  int64_t target_wgs = (int64_t)cus * (mla ? 4 : 6);
   int64_t per_head_chunks = std::max<int64_t>(1, target_wgs / std::max(1, Hkv));
   int64_t c = (sum_units + per_head_chunks - 1) / per_head_chunks;
   c = (c + round - 1) / round * round;
@@ -196,8 +199,20 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
   const int chunk_tiles = decode_chunk_units(sum_tiles, g.Hkv, ds.active_cus, mla);
   const int max_chunks = (max_tiles + chunk_tiles - 1) / chunk_tiles;
 
+  // work items (request, chunk), longest first: only chunks that exist are launched
+  struct Item { int32_t req, chunk, units; };
+  std::vector<Item> items;
+  for (int r = 0; r < B; ++r) {
+    const int32_t units = (b->ctx_lens[r] + unit_t - 1) / unit_t;
+    for (int32_t ck = 0; ck * chunk_tiles < units; ++ck)
+      items.push_back(Item{r, ck, std::min<int32_t>(chunk_tiles, units - ck * chunk_tiles)});
+  }
+  std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& c) { return a.units > c.units; });
+  const int n_items = (int)items.size();
+
   size_t off_bt = align16(sizeof(int32_t) * (size_t)B);
-  size_t off_desc = align16(off_bt + sizeof(int32_t) * (size_t)B * bt_stride);
+  size_t off_items = align16(off_bt + sizeof(int32_t) * (size_t)B * bt_stride);
+  size_t off_desc = align16(off_items + sizeof(int32_t) * 2 * (size_t)n_items);
   size_t bytes = off_desc + (append ? sizeof(TileDesc) * (size_t)B : 0);
   spd_stage* st;
   if ((rc = stage_acquire(ctx, SPD_PHASE_DECODE, bytes, &st)) != SPD_OK) return rc;
@@ -209,6 +224,11 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
 
   int32_t* h_ctx = (int32_t*)st->host;
   int32_t* h_bt = (int32_t*)(st->host + off_bt);
+  int32_t* h_items = (int32_t*)(st->host + off_items);
+  for (int i = 0; i < n_items; ++i) {
+    h_items[2 * i] = items[(size_t)i].req;
+    h_items[2 * i + 1] = items[(size_t)i].chunk;
+  }
   TileDesc* h_desc = (TileDesc*)(st->host + off_desc);
   {
     std::lock_guard<std::mutex> lk(pool->mu);                       // atomic: query, get, update
@@ -237,21 +257,23 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
       }
     }
   }
-  SPD_HIP(hipEventRecord(ds.ev_start, stream));
+  if (ctx->kernel_timing) SPD_HIP(hipEventRecord(ds.ev_start, stream));
   if ((rc = stage_commit(ctx, SPD_PHASE_DECODE, st, bytes, stream)) != SPD_OK) return rc;
   if (append)
     SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(st->dev + off_desc), B, b->k_new, b->v_new, stream));
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 0, stream)) != SPD_OK) return rc;
   if (mla)
     SPD_HIP(launch_decode_mla(g, pool->base, b->q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
-                              bt_stride, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks, (float*)ws,
-                              (float*)(ws ? ws + ws_o_bytes : nullptr), stream));
+                              bt_stride, st->dev + off_items, n_items, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks,
+                              (float*)ws, (float*)(ws ? ws + ws_o_bytes : nullptr), stream));
   else
     SPD_HIP(launch_decode_gqa(g, pool->base, b->q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
-                              bt_stride, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks, (float*)ws,
-                              (float*)(ws ? ws + ws_o_bytes : nullptr), stream));
+                              bt_stride, st->dev + off_items, n_items, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks,
+                              (float*)ws, (float*)(ws ? ws + ws_o_bytes : nullptr), stream));
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 1, stream)) != SPD_OK) return rc;
-  SPD_HIP(hipEventRecord(ds.ev_end, stream));
-  ds.timed = true;
+  if (ctx->kernel_timing) {
+    SPD_HIP(hipEventRecord(ds.ev_end, stream));
+    ds.timed = true;
+  }
   return SPD_OK;
 }
