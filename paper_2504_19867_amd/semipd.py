@@ -2,8 +2,11 @@
 
 Every step of the hot path runs inside the library's HIP kernels.  Device buffers are passed
 as integer addresses (e.g. ``tensor.data_ptr()``); PyTorch is only the caller's way to own
-device memory and is not imported here.  There is no CPU fallback: if the library is missing
-the import fails.
+device memory.  There is no CPU fallback: if the library is missing the import fails.
+
+PyTorch ships its own copy of the HIP runtime.  A process must use ONE runtime for the tensors
+and for this library (a second copy finds no device), so when PyTorch is installed it is imported
+first: the library's dependency on libamdhip64 then resolves to the copy PyTorch has loaded.
 """
 from __future__ import annotations
 
@@ -59,6 +62,10 @@ class spd_decode_batch(C.Structure):
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+    try:
+        import torch  # noqa: F401  (loads PyTorch's HIP runtime first, see the module docstring)
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
     P = C.POINTER
