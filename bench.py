@@ -22,6 +22,9 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PRE, DEC = 0, 1
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated against a plain copy
+# kernel of known size (profiles/c2_hbm_traffic_pmc.md); keyed by workload, (prefill kernel, decode kernels)
+MEASURED_TRAFFIC = {"c2_llama3_8b": (100.9e6 + 67.1e6, 571.1e6 + 2.2e6)}
 
 
 def parse():
@@ -35,6 +38,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--pool-gb", type=float, default=None, help="override pool size (GB)")
     ap.add_argument("--no-scramble", action="store_true", help="experiment: hand out physical pages in order")
+    ap.add_argument("--decode-per-prefill", type=int, default=0,
+                    help="fix r (decode steps per prefill step) and skip the solo calibration passes (profiling aid)")
     ap.add_argument("--only", default=None, choices=[None, "prefill", "decode"],
                     help="profiling aid: run only one phase in the timed region")
     return ap.parse_args()
@@ -128,6 +133,12 @@ class Bench:
             qo_bytes = self.B * L.n_q_heads * (L.dim_qk + L.dim_v) * 2
         self.decode_bytes = float(kv_bytes + qo_bytes)
         self.n_pre = self.n_dec = 0
+
+    def close(self):
+        self.sync()
+        self.pre_batches = self.dec_batches = None
+        self.pool.close()
+        self.ctx.close()
 
     def prefill(self):
         self.pool.prefill_step_batch(self.pre_batches[self.n_pre % 2])
@@ -263,9 +274,13 @@ def main():
     def measure_split(pp, dp, steps, warmup, only=None):
         p_cus, d_cus = bench.set_split(pp, dp)
         copy_gbs = bench.copy_ceiling(DEC)
-        solo_p_k, solo_p_w = bench.time_solo(PRE, max(5, steps // 4))
-        solo_d_k, solo_d_w = bench.time_solo(DEC, max(10, steps))
-        r = max(1, round(solo_p_w / solo_d_w))
+        if args.decode_per_prefill > 0:
+            r = args.decode_per_prefill
+            solo_p_k = solo_p_w = solo_d_k = solo_d_w = float("nan")
+        else:
+            solo_p_k, solo_p_w = bench.time_solo(PRE, max(5, steps // 4))
+            solo_d_k, solo_d_w = bench.time_solo(DEC, max(10, steps))
+            r = max(1, round(solo_p_w / solo_d_w))
         bench.run_concurrent(warmup, r, only)
         wall_ms, _, _ = bench.run_concurrent(steps, r, only)                       # the timed region: K steps
         _, pk, dk = bench.run_concurrent(min(steps, 64), r, only, timing=True)     # same steps again, kernels bracketed by events
@@ -306,19 +321,22 @@ def main():
         "prefill_tok_s": head["prefill_tok_s"], "decode_tok_s": head["decode_tok_s"],
         "roofline": {"bound": "mfma", "kernel": f"prefill_kernel<{cfg.layer.dim_qk},{cfg.layer.dim_v}>", "achieved": head["prefill_tflops"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": (head["prefill_tflops"] or 0.0) / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": (head["prefill_tflops"] or 0.0) / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC.get(cfg.name, (None, None))[0],
                      "kernel_ms": pre_ms, "flops_per_launch": bench.prefill_flops,
                      "share_cus": head["prefill_cus"],
                      "frac_of_share_peak": (head["prefill_tflops"] or 0.0) / (PEAK_BF16_TFLOPS * head["prefill_cus"] / bench.total_cus)},
         "roofline_decode": {"bound": "hbm", "kernel": ("decode_mla_kernel" if cfg.layer.kind == "mla" else f"decode_gqa_kernel<{cfg.layer.dim_qk}>") + " (+combine)", "achieved": head["decode_gbs"],
                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": (head["decode_gbs"] or 0.0) / PEAK_HBM_GBS,
-                            "traffic": None, "kernel_ms": head["decode_kernel_ms"],
+                            "traffic": MEASURED_TRAFFIC.get(cfg.name, (None, None))[1], "kernel_ms": head["decode_kernel_ms"],
                             "bytes_per_launch": bench.decode_bytes, "share_cus": head["decode_cus"]},
         "splits": splits,
     }
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cfg, r)
     print(json.dumps(result))
+    sys.stdout.flush()
+    bench.close()
 
 
 if __name__ == "__main__":
