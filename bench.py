@@ -10,6 +10,7 @@ Workload: benchmark configs[1] (Llama-3-8B attention layer shape).  Prints O
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import math
 import os
@@ -179,11 +180,14 @@ class Bench:
         for _ in range(3):
             fn()
         self.ctx.phase_sync(phase)
+        gc.collect()
+        gc.disable()                  # a full collection of the driver's Python heap is a 6 ms pause
         t0 = time.perf_counter()
         for _ in range(n):
             fn()
         self.ctx.phase_sync(phase)
         wall = (time.perf_counter() - t0) * 1e3 / n
+        gc.enable()
         self.ctx.set_kernel_timing(True)
         self.ctx.phase_kernel_ms(phase)
         for _ in range(n):
@@ -200,6 +204,8 @@ class Bench:
         self.ctx.set_kernel_timing(timing)
         self.ctx.phase_kernel_ms(PRE); self.ctx.phase_kernel_ms(DEC)
         torch.cuda.synchronize()
+        gc.collect()
+        gc.disable()                  # keep the Python driver's collector out of the timed region
         t0 = time.perf_counter()
         for _ in range(steps):
             if only != "decode":
@@ -210,6 +216,7 @@ class Bench:
         self.sync()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        gc.enable()
         pk, dk = self.ctx.phase_kernel_ms(PRE), self.ctx.phase_kernel_ms(DEC)
         self.ctx.set_kernel_timing(False)
         return wall_ms, pk, dk

@@ -118,6 +118,9 @@ struct spd_phase_state {
   bool timed = false;
   char* workspace = nullptr;           // split-K partials (decode)
   size_t ws_cap = 0;
+  // last split-K chunk choice of the MLA decode (re-derived when the batch has changed by more than a little)
+  int ck_B = 0, ck_cus = 0, ck_chunk = 0;
+  int64_t ck_sum = 0;
   hipEvent_t kev[256][2] = {};         // kernel timing ring (measurement aid)
   uint64_t kev_count = 0, kev_read = 0;
 };

@@ -9,15 +9,22 @@
 // the tokens).  34.8 kflop per 1152-byte row: the fp32 vector units cannot keep up with HBM, the
 // matrix cores must; the heads (<= 16) are the MFMA column dimension.
 //
-// One workgroup (4 waves) owns one (request, chunk of the context).  Steps of 32 tokens (36 KiB,
+// One workgroup (4 waves) owns one (request, chunk of the context).  Steps of 16 tokens (18 KiB,
 // contiguous in the page: latent pages keep the natural [token][dim] order) stream
-// HBM -> LDS with global_load_lds_dwordx4 into a 4-stage ring, 3 steps (108 KiB per CU) ahead.
+// HBM -> LDS with global_load_lds_dwordx4 into a 4-stage ring, 3 steps ahead.  The ring takes
+// 72 KiB, so two workgroups share a CU: 108 KiB are in flight per CU, and one workgroup's
+// waits and start-up are covered by the other one's arithmetic.
 // Out of LDS the rows are read twice, in the two operand orders:
 //     S^T[token, head] = C[16 x 576] . Q^T[576 x 16]      ds_read_b128     + v_mfma_f32_16x16x32_bf16
 //     O^T[dim, head]  += C^T[16 dims x 16 tokens] . P^T    ds_read_b64_tr_b16 + v_mfma_f32_16x16x16_bf16
 // Every wave computes the (small) score product and the softmax statistics redundantly and owns
 // 128 of the 512 output dims, so no cross-wave reduction is ever needed.  Split-K partials go to
 // the same workspace / combine kernel as the GQA path.
+//
+// With one wave per SIMD nothing hides latency but the wave's own instruction stream, so both
+// products are software-pipelined: LDS operand reads run a ring of 8 operands ahead of the MFMAs,
+// and the score product accumulates into six independent accumulators (three per 16-token block)
+// so that back-to-back MFMAs never wait for each other's result.
 #include "internal.h"
 
 namespace spd {
@@ -34,13 +41,13 @@ constexpr int DL = 576;               // latent dims per token
 constexpr int DV = 512;               // leading dims that act as values
 constexpr int ROW_BYTES = DL * 2;     // 1152
 constexpr int CH = DL / 8;            // 72 16-byte chunks per row
-constexpr int STEP_T = 32;            // tokens per step
-constexpr int STAGE_BYTES = STEP_T * ROW_BYTES;   // 36864
+constexpr int STEP_T = 16;            // tokens per step
+constexpr int STAGE_BYTES = STEP_T * ROW_BYTES;   // 18432
 constexpr int NSTAGE = 4;
 constexpr int PD = NSTAGE - 1;
-constexpr int NI = STAGE_BYTES / 1024;            // 36 load instructions per step
+constexpr int NI = STAGE_BYTES / 1024;            // 18 load instructions per step
 constexpr int WAVES = 4;
-constexpr int LPW = NI / WAVES;                   // 9
+constexpr int LPW = (NI + WAVES - 1) / WAVES;     // 5 for waves 0 and 1, 4 for waves 2 and 3
 constexpr int KS = DL / 32;                       // 18 k-steps of the score product
 constexpr int VB = DV / 16 / WAVES;               // 8 value blocks of 16 dims per wave
 }  // namespace mla
@@ -51,10 +58,30 @@ __device__ inline uint32_t mla_pack_bf16(float a, float b) {
 __device__ inline void mla_dma16(const void* gptr, uint32_t lds_byte_addr) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte_addr), "v"(gptr) : "memory");
 }
+// The same with the address split in a wave-uniform base and a 32-bit per-lane offset.
+__device__ inline void mla_dma16s(const void* sbase, uint32_t voff, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase) : "memory");
+}
+// max over the four 16-lane rows of a wave, on the vector ALU: the row swaps exchange odd rows of
+// the first register with even rows of the second (rows of 16, then of 32 lanes)
+__device__ inline float mla_max_over_rows(float x) {
+  float y = x;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(x), "+v"(y));
+  x = fmaxf(x, y);
+  y = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(x), "+v"(y));
+  return fmaxf(x, y);
+}
+#ifdef SPD_MLA_STAMPS
+__device__ unsigned long long g_mla_ph[8];
+#define MLA_STAMP(i) { unsigned long long now_ = __builtin_readcyclecounter(); ph[i] += now_ - tprev; tprev = now_; }
+#else
+#define MLA_STAMP(i)
+#endif
 #define SPD_MLA_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
 
-// grid (n_items), block 256: work item = (request, chunk).  chunk_steps = 32-token steps per chunk.
-__global__ __launch_bounds__(256, 1) void decode_mla_kernel(
+// grid (n_items), block 256: work item = (request, chunk).  chunk_steps = 16-token steps per chunk.
+__global__ __launch_bounds__(256, 2) void decode_mla_kernel(
     const char* __restrict__ pool, uint64_t page_bytes, int steps_per_page, const bf16_t* __restrict__ q,
     bf16_t* __restrict__ out, const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ bt, int bt_stride,
     const int2* __restrict__ items, int H, float c /* scale * log2(e) */, int chunk_steps, int max_chunks, float* __restrict__ ws_o,
@@ -86,22 +113,32 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(
 
   // ---- loads: instruction ii = wave + 4 j fills LDS slots [64 ii, 64 ii + 64) of the stage;
   // slot s of row r holds the row's chunk s ^ (r & 7)
-  int ld_off[LPW];
+  uint32_t ld_off[LPW];
 #pragma unroll
   for (int j = 0; j < LPW; ++j) {
     const int slot = (wave + WAVES * j) * 64 + lane, row = slot / CH, sl = slot % CH;
-    ld_off[j] = row * ROW_BYTES + ((sl ^ (row & 7)) * 16);
+    ld_off[j] = (uint32_t)(row * ROW_BYTES + ((sl ^ (row & 7)) * 16));
   }
-  auto issue_loads = [&](int st) {            // st: step index inside the chunk
+  const bool five = wave + WAVES * (LPW - 1) < NI;   // this wave issues LPW loads per step (else LPW - 1)
+  // A step's loads: the wave-uniform source address and LDS stage first, then the instructions.
+  // A load instruction occupies the CU's address unit for 16 cycles, and the wave that issues it
+  // stalls meanwhile: in the loop they are handed out one at a time between MFMAs.
+  auto load_src = [&](int st) -> const char* {
     const int gs = step0 + st;
     const int page = bt_row[gs / steps_per_page];
-    const char* src = pool + (uint64_t)page * page_bytes + (size_t)(gs % steps_per_page) * STAGE_BYTES;
-    const uint32_t stage = smem_base + (uint32_t)(st % NSTAGE) * STAGE_BYTES;
+    return pool + (uint64_t)page * page_bytes + (size_t)(gs % steps_per_page) * STAGE_BYTES;
+  };
+  auto load_one = [&](const char* src, int st, int j) {
+    if (j < LPW - 1 || five)
+      mla_dma16s(src, ld_off[j], smem_base + (uint32_t)(st % NSTAGE) * STAGE_BYTES + (uint32_t)(wave + WAVES * j) * 1024);
+  };
+  auto issue_loads = [&](int st) {            // st: step index inside the chunk
+    const char* src = load_src(st);
 #pragma unroll
-    for (int j = 0; j < LPW; ++j) mla_dma16(src + ld_off[j], stage + (uint32_t)(wave + WAVES * j) * 1024);
+    for (int j = 0; j < LPW; ++j) load_one(src, st, j);
   };
 
-  // ---- LDS operand addresses (byte offsets inside a stage, for the first 16-token block)
+  // ---- LDS operand addresses (byte offsets inside a stage)
   // score operand (k-step s): row = col, chunk 4 s + c4  ->  slot (4 s + c4) ^ (col & 7);
   // bit 2 of the swizzle flips the parity of s, hence two bases (even / odd s) + 128 * (s / 2)
   const int f = (col >> 2) & 1;
@@ -111,7 +148,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(
   // and dims 4 (r % 4) .. + 3; the transpose read hands lane i dim i of those 4 tokens
   const int v_row = 4 * c4 + (col >> 2);
   const int v_sw = v_row & 7;
-  int v_base[4];                                   // by blk & 3; add 128 * (blk / 4) + 2048 * wave ... (below)
+  int v_base[4];                                   // by blk & 3; add 128 * (blk / 4)
 #pragma unroll
   for (int b3 = 0; b3 < 4; ++b3) {
     const int ch_low = (2 * b3 + ((col & 3) >> 1)) ^ v_sw;         // low three bits of the chunk index
@@ -126,56 +163,88 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(
 #pragma unroll
   for (int t = 0; t < PD; ++t)
     if (t < n_steps) issue_loads(t);
+  // Draw the compiler's wait for the query loads to this point, after the first steps are on their
+  // way: left to itself it waits at their first use inside the loop, with a count that knows
+  // nothing of the loads issued by hand, and every iteration would drain the prefetch queue.
+#pragma unroll
+  for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(__builtin_bit_cast(uint4, qf[s]).x));
 
+  constexpr int RING = 8;
+  static_assert(RING == VB, "all value operands of a step are read ahead");
+#ifdef SPD_MLA_STAMPS
+  unsigned long long ph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  unsigned long long tprev = __builtin_readcyclecounter();
+#endif
   for (int st = 0; st < n_steps; ++st) {
+    MLA_STAMP(0)
+    // this wave's loads of step st are done when at most (steps issued after it) * (its loads per step) remain
     const int later = min(PD - 1, n_steps - 1 - st);
-    if (later >= 2) SPD_MLA_WAIT_VMCNT(2 * LPW);
-    else if (later == 1) SPD_MLA_WAIT_VMCNT(LPW);
-    else SPD_MLA_WAIT_VMCNT(0);
+    if (five) {
+      if (later >= 2) SPD_MLA_WAIT_VMCNT(2 * LPW);
+      else if (later == 1) SPD_MLA_WAIT_VMCNT(LPW);
+      else SPD_MLA_WAIT_VMCNT(0);
+    } else {
+      if (later >= 2) SPD_MLA_WAIT_VMCNT(2 * (LPW - 1));
+      else if (later == 1) SPD_MLA_WAIT_VMCNT(LPW - 1);
+      else SPD_MLA_WAIT_VMCNT(0);
+    }
+    MLA_STAMP(1)
     asm volatile("s_barrier" ::: "memory");        // step st has landed for all waves; stage of st - 1 is free
-    if (st + PD < n_steps) issue_loads(st + PD);
+    MLA_STAMP(2)
+    const bool more = st + PD < n_steps;
+    const char* src_next = load_src(more ? st + PD : st);
+    MLA_STAMP(3)
 
     const char* stage = smem + (st % NSTAGE) * STAGE_BYTES;
     const int tok0 = (step0 + st) * STEP_T;         // first token of the step
-    // ---- S^T = C . Q^T for the two 16-token blocks
-    f32x4 S[2];
+    auto read_s = [&](int sk) -> uint4 {
+      return *(const uint4*)(stage + ((sk & 1) ? k_odd : k_even) + 128 * (sk >> 1));
+    };
+    auto read_v = [&](int blk) -> s16x4 {
+      return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(stage + v_base[blk & 3] + 128 * (blk >> 2)));
+    };
+
+    // ---- S^T = C . Q^T: k-step sk accumulates into accumulator sk % 3, so that back-to-back
+    // MFMAs never wait for each other's result.  The loads of step st + PD go out between the
+    // MFMAs, one every third.
+    f32x4 acc[3];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      S[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-      const char* rowp = stage + u * (16 * ROW_BYTES);
+    for (int i = 0; i < 3; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    uint4 ring[RING];
 #pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        const uint4 a = *(const uint4*)(rowp + ((s & 1) ? k_odd : k_even) + 128 * (s >> 1));
-        S[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), qf[s], S[u], 0, 0, 0);
-      }
+    for (int o = 0; o < RING; ++o) ring[o] = read_s(o);
+    __builtin_amdgcn_sched_barrier(0);              // keep the issue order below (reads stay ahead of their use)
+#pragma unroll
+    for (int sk = 0; sk < KS; ++sk) {
+      acc[sk % 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ring[sk % RING]), qf[sk], acc[sk % 3], 0, 0, 0);
+      if (sk + RING < KS) ring[sk % RING] = read_s(sk + RING);
+      if (sk % 3 == 1 && sk / 3 < LPW && more) load_one(src_next, st + PD, sk / 3);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    // lane holds, for head col, tokens tok0 + 16 u + 4 c4 + i
-    if (tok0 + STEP_T > n) {
+    MLA_STAMP(4)
+    // value operands: in flight while the vector ALU does the softmax
+    s16x4 vring[RING];
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+    for (int o = 0; o < RING; ++o) vring[o] = read_v(o);
+    __builtin_amdgcn_sched_barrier(0);
+    f32x4 S = acc[0] + acc[1] + acc[2];
+    // lane holds, for head col, tokens tok0 + 4 c4 + i
+    const bool tail = tok0 + STEP_T > n;
+    if (tail) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (tok0 + 16 * u + 4 * c4 + i >= n) S[u][i] = -INFINITY;
+      for (int i = 0; i < 4; ++i)
+        if (tok0 + 4 * c4 + i >= n) S[i] = -INFINITY;
     }
-    float mx = fmaxf(fmaxf(fmaxf(S[0][0], S[0][1]), fmaxf(S[0][2], S[0][3])),
-                     fmaxf(fmaxf(S[1][0], S[1][1]), fmaxf(S[1][2], S[1][3])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    float mx = fmaxf(fmaxf(S[0], S[1]), fmaxf(S[2], S[3]));
+    mx = mla_max_over_rows(mx);
     const float m_new = fmaxf(m, mx);
     const float mc = m_new * c;
-    float psum = 0.f;
-    uint2 pb[2];
+    float p[4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      float p[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        p[i] = __builtin_amdgcn_exp2f(S[u][i] * c - mc);
-        psum += p[i];
-      }
-      pb[u].x = mla_pack_bf16(p[0], p[1]);
-      pb[u].y = mla_pack_bf16(p[2], p[3]);
-    }
+    for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(S[i] * c - mc);
+    const float psum = (p[0] + p[1]) + (p[2] + p[3]);
+    const uint2 pb = uint2{mla_pack_bf16(p[0], p[1]), mla_pack_bf16(p[2], p[3])};
     if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {        // rescale only when some running maximum moved
       const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
       l *= alpha;
@@ -184,29 +253,34 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(
       m = m_new;
     }
     l += psum;
-    // ---- O^T += C^T . P^T for this wave's 128 dims
+    // ---- O^T += C^T . P^T for this wave's 128 dims.  Tokens of this lane's operand:
+    // tok0 + 4 c4 + {0..3}; slots past the context hold arbitrary bytes and are cleared.
+    MLA_STAMP(5)
+    __builtin_amdgcn_sched_barrier(0);
+    if (!tail) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      // tokens of this lane's operand: tok0 + 16 u + 4 c4 + {0..3}; slots past the context hold arbitrary bytes
-      const int t0 = tok0 + 16 * u + 4 * c4;
-      const bool vtail = t0 + 4 > n;
+      for (int blk = 0; blk < VB; ++blk)
+        O[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vring[blk], __builtin_bit_cast(s16x4, pb), O[blk], 0, 0, 0);
+    } else {                                        // last step of the context
+      const int t0 = tok0 + 4 * c4;
       const uint32_t m01 = (t0 + 0 < n ? 0x0000ffffu : 0u) | (t0 + 1 < n ? 0xffff0000u : 0u);
       const uint32_t m23 = (t0 + 2 < n ? 0x0000ffffu : 0u) | (t0 + 3 < n ? 0xffff0000u : 0u);
-      const s16x4 pv = __builtin_bit_cast(s16x4, pb[u]);
 #pragma unroll
       for (int blk = 0; blk < VB; ++blk) {
-        s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(
-            stage + u * (16 * ROW_BYTES) + v_base[blk & 3] + 128 * (blk >> 2)));
-        if (vtail) {
-          uint2 r = __builtin_bit_cast(uint2, a);
-          r.x &= m01;
-          r.y &= m23;
-          a = __builtin_bit_cast(s16x4, r);
-        }
-        O[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, pv, O[blk], 0, 0, 0);
+        uint2 r = __builtin_bit_cast(uint2, vring[blk]);
+        r.x &= m01;
+        r.y &= m23;
+        O[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, r), __builtin_bit_cast(s16x4, pb), O[blk], 0, 0, 0);
       }
     }
+    MLA_STAMP(6)
   }
+#ifdef SPD_MLA_STAMPS
+  if (lane == 0 && wave == 1) {
+    for (int i = 0; i < 7; ++i) atomicAdd(&g_mla_ph[i], ph[i]);
+    atomicAdd(&g_mla_ph[7], (unsigned long long)n_steps);
+  }
+#endif
 
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
@@ -257,6 +331,14 @@ __global__ __launch_bounds__(512) void decode_mla_combine_kernel(bf16_t* __restr
   out[((size_t)b * H + h) * mla::DV + d] = (bf16_t)(mla_pack_bf16(o / l_tot, 0.f) & 0xffffu);
 }
 
+#ifdef SPD_MLA_STAMPS
+extern "C" int spd_debug_mla_phases(unsigned long long* out8, int reset) {
+  unsigned long long z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_mla_ph), sizeof(z)) != hipSuccess) return -1;
+  if (reset && hipMemcpyToSymbol(HIP_SYMBOL(g_mla_ph), z, sizeof(z)) != hipSuccess) return -1;
+  return 0;
+}
+#endif
 int decode_mla_step_tokens() { return mla::STEP_T; }
 
 hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const void* q, void* out,

@@ -47,6 +47,10 @@ __device__ inline uint32_t cvt_pk_bf16(float a, float b) {
 __device__ inline void dma16(const void* gptr, uint32_t lds_byte_addr) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte_addr), "v"(gptr) : "memory");
 }
+// The same with the address split in a wave-uniform base and a 32-bit per-lane offset.
+__device__ inline void dma16s(const void* sbase, uint32_t voff, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase) : "memory");
+}
 // s_waitcnt vmcnt(N) only (expcnt and lgkmcnt fields left at their maxima)
 #define SPD_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
 
@@ -105,29 +109,50 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
   // ---- tile loads.  Load instruction ii = wave + 8 j (j < LPW) fills the 64 consecutive 16-byte
   // slots [64 ii, 64 ii + 64) of the stage: K slots first (row = slot / CHK), then V slots.
   // Slot s of a row holds the row's chunk s ^ swz(row).
-  int ld_row[LPW], ld_coff[LPW];                // tile row and byte offset inside the global row
-#pragma unroll
-  for (int j = 0; j < LPW; ++j) {
+  // The per-lane part of the address does not depend on the tile (except past the prompt's end).
+  auto slot_of = [&](int j, int& row, int& coff, uint32_t& pitch) {
     const int ii = wave + WAVES * j;
     if (ii < CHK) {
-      const int slot = ii * 64 + lane, row = slot / CHK, sl = slot % CHK;
-      ld_row[j] = row;
-      ld_coff[j] = (sl ^ k_swz<DQK>(row)) * 16;
+      const int slot = ii * 64 + lane, sl = slot % CHK;
+      row = slot / CHK;
+      coff = (sl ^ k_swz<DQK>(row)) * 16;
+      pitch = k_pitch;
     } else {
-      const int slot = (ii - CHK) * 64 + lane, row = slot / CHV, sl = slot % CHV;
-      ld_row[j] = row;
-      ld_coff[j] = (sl ^ v_swz<DV>(row)) * 16;
+      const int slot = (ii - CHK) * 64 + lane, sl = slot % CHV;
+      row = slot / CHV;
+      coff = (sl ^ v_swz<DV>(row)) * 16;
+      pitch = v_pitch;
     }
+  };
+  uint32_t ld_voff[LPW];
+#pragma unroll
+  for (int j = 0; j < LPW; ++j) {
+    int row, coff;
+    uint32_t pitch;
+    slot_of(j, row, coff, pitch);
+    ld_voff[j] = (uint32_t)row * pitch + (uint32_t)coff;
   }
   auto issue_loads = [&](int kt) {
     const int kv0 = kt * BN;
     const uint32_t stage = smem_base + (uint32_t)(kt % NSTAGE) * STAGE_BYTES;
+    const char* kb = kbase + (size_t)kv0 * k_pitch;
+    const char* vb = vbase + (size_t)kv0 * v_pitch;
+    if (kv0 + BN <= w.len) {
 #pragma unroll
-    for (int j = 0; j < LPW; ++j) {
-      const int ii = wave + WAVES * j;
-      const int key = min(kv0 + ld_row[j], w.len - 1);          // rows past the prompt re-read its last row
-      const char* src = (ii < CHK) ? kbase + (size_t)key * k_pitch + ld_coff[j] : vbase + (size_t)key * v_pitch + ld_coff[j];
-      dma16(src, stage + (uint32_t)ii * 1024);
+      for (int j = 0; j < LPW; ++j) {
+        const int ii = wave + WAVES * j;
+        dma16s(ii < CHK ? kb : vb, ld_voff[j], stage + (uint32_t)ii * 1024);
+      }
+    } else {                                    // rows past the prompt re-read its last row
+      const int last = w.len - 1 - kv0;
+#pragma unroll
+      for (int j = 0; j < LPW; ++j) {
+        const int ii = wave + WAVES * j;
+        int row, coff;
+        uint32_t pitch;
+        slot_of(j, row, coff, pitch);
+        dma16s(ii < CHK ? kb : vb, (uint32_t)min(row, last) * pitch + (uint32_t)coff, stage + (uint32_t)ii * 1024);
+      }
     }
   };
 
@@ -158,6 +183,12 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
 #pragma unroll
   for (int t = 0; t < PD; ++t)
     if (t < n_kv_tiles) issue_loads(t);
+  // Draw the compiler's wait for the Q loads to this point, after the first tiles are on their
+  // way.  Left to itself it waits at their first use, inside the tile loop, with a count that
+  // knows nothing of the tile loads issued by hand: every iteration would then drain the whole
+  // prefetch queue.
+#pragma unroll
+  for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(__builtin_bit_cast(uint4, qf[s]).x));
 
   for (int kt = 0; kt < n_kv_tiles; ++kt) {
     const int kv0 = kt * BN;
@@ -217,7 +248,14 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[0][i]);
 #pragma unroll
     for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[1][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    {
+      // the other half of the wave holds the other 32 keys of the same query: exchange on the
+      // vector ALU (swap of the upper half of one register with the lower half of another;
+      // written as machine code: the compiler's builtin for it loses the second result)
+      float mx2 = mx;
+      asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(mx), "+v"(mx2));
+      mx = fmaxf(mx, mx2);
+    }
     const float m_new = fmaxf(m, mx);
     const float mc = m_new * c;
     float psum = 0.f;

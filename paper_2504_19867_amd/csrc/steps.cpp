@@ -8,6 +8,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <functional>
 #include <cmath>
 
 using namespace spd;
@@ -147,19 +148,54 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
 }
 
 // ------------------------------------------------------------------------------------------ decode
-// Split-K chunk length in units (16-token tiles for GQA, 32-token steps for MLA).
-static int decode_chunk_units(int64_t sum_units, int Hkv, int cus, bool mla) {
+// Split-K chunk length in units (16-token tiles for GQA, 16-token steps for MLA).
+static int decode_chunk_units(spd_phase_state& ps, const int32_t* ctx_lens, int B, int unit_t, int64_t sum_units, int Hkv,
+                              int cus, bool mla) {
   const char* env = getenv("SPD_DECODE_CHUNK_TILES");   // tuning override, read per call
   const int64_t round = mla ? 1 : 8;              // GQA: 4 waves x 2 tiles per step
   if (env && atoi(env) > 0) return (int)((atoi(env) + round - 1) / round * round);
-  // aim at ~6 (GQA, two workgroups per CU) or ~4 (MLA, one per CU) workgroups per CU of the decode
-  // share: enough to balance unequal contexts (items are issued longest first), few enough to keep
-  // the split-K partials small
-  int64_t target_wgs = (int64_t)cus * (mla ? 4 : 6);
+  if (mla) {
+    // Two workgroups are resident per CU (slots); items are issued longest first and a slot takes
+    // the next item when it is done, so a chunk length is judged by replaying exactly that: the
+    // candidate with the shortest finish time wins.  An item costs its steps plus a pipeline
+    // fill.  The choice is kept while the batch stays about the same.
+    if (ps.ck_chunk > 0 && ps.ck_B == B && ps.ck_cus == cus && llabs(sum_units - ps.ck_sum) * 32 <= ps.ck_sum)
+      return ps.ck_chunk;
+    const int slots = std::max(1, 2 * cus);
+    const int64_t fill = 6;
+    const int64_t c_min = std::max<int64_t>(8, (sum_units + slots - 1) / slots);
+    int64_t best_c = c_min, best_t = INT64_MAX;
+    std::vector<int32_t> sizes;
+    std::vector<int64_t> heap;
+    for (int k = 0; k < 16; ++k) {
+      const int64_t c = c_min + c_min * k / 6;    // c_min .. 3.5 c_min
+      sizes.clear();
+      for (int r = 0; r < B; ++r) {
+        int32_t u = (ctx_lens[r] + unit_t - 1) / unit_t;
+        for (; u > 0; u -= (int32_t)c) sizes.push_back((int32_t)std::min<int64_t>(u, c));
+      }
+      std::sort(sizes.begin(), sizes.end(), std::greater<int32_t>());
+      heap.assign((size_t)slots, 0);              // min-heap of slot finish times
+      auto cmp = std::greater<int64_t>();
+      int64_t finish = 0;
+      for (int32_t sz : sizes) {
+        std::pop_heap(heap.begin(), heap.end(), cmp);
+        heap.back() += sz + fill;
+        finish = std::max(finish, heap.back());
+        std::push_heap(heap.begin(), heap.end(), cmp);
+      }
+      if (finish < best_t) { best_t = finish; best_c = c; }
+    }
+    ps.ck_B = B; ps.ck_cus = cus; ps.ck_sum = sum_units; ps.ck_chunk = (int)std::min<int64_t>(best_c, 1 << 20);
+    return ps.ck_chunk;
+  }
+  // GQA: aim at ~6 workgroups per CU of the decode share: enough to balance unequal contexts
+  // (items are issued longest first), few enough to keep the split-K partials small
+  int64_t target_wgs = (int64_t)cus * 6;
   int64_t per_head_chunks = std::max<int64_t>(1, target_wgs / std::max(1, Hkv));
   int64_t c = (sum_units + per_head_chunks - 1) / per_head_chunks;
   c = (c + round - 1) / round * round;
-  return (int)std::min<int64_t>(std::max<int64_t>(c, mla ? 8 : 16), 1 << 20);
+  return (int)std::min<int64_t>(std::max<int64_t>(c, 16), 1 << 20);
 }
 
 extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* b) {
@@ -196,7 +232,7 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
   int rc = phase_enter(ctx, SPD_PHASE_DECODE, &stream);
   if (rc != SPD_OK) return rc;
   spd_phase_state& ds = ctx->phase[SPD_PHASE_DECODE];
-  const int chunk_tiles = decode_chunk_units(sum_tiles, g.Hkv, ds.active_cus, mla);
+  const int chunk_tiles = decode_chunk_units(ds, b->ctx_lens, B, unit_t, sum_tiles, g.Hkv, ds.active_cus, mla);
   const int max_chunks = (max_tiles + chunk_tiles - 1) / chunk_tiles;
 
   // work items (request, chunk), longest first: only chunks that exist are launched

@@ -15,7 +15,7 @@ import os
 from typing import List, Optional, Sequence, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsemipd.so")
+LIB_PATH = os.environ.get("SEMIPD_LIB", os.path.join(_HERE, "libsemipd.so"))   # override: a differently built library
 
 SPD_OK, SPD_EINVAL, SPD_ENOMEM, SPD_ENOENT, SPD_EHIP, SPD_ESTATE = 0, -1, -2, -3, -5, -6
 SPD_PHASE_PREFILL, SPD_PHASE_DECODE = 0, 1
