@@ -238,6 +238,47 @@ int spd_partition_masks(int total_cus, int granularity, int prefill_cus, int dec
  * them; used to check that a masked stream stays on its CUs. */
 int spd_phase_probe_cus(spd_ctx* ctx, int phase, int32_t n_blocks, int32_t* ids, int32_t cap, int32_t* n_ids);
 
+/* ------------------------------------------------------------- SLO-aware partition adjuster
+ * Paper, "Dynamic Adjusting Method": Algorithm 1 (SLO-aware adjusting algorithm) with the
+ * latency models of Eq. 4, TTFT_x = a1 / (x - lambda) + b1 and TPOT_y = a2 / y + b2, learned
+ * online from observed latencies (Eq. 1-3 give their shape).  Host logic only: the caller feeds
+ * latencies, asks once per iteration for the partition to use, and passes a changed answer to
+ * spd_set_partition (shares are percentages of the GPU's CUs).
+ *
+ * Where the printed algorithm is broken or silent this library: increments the step counter once
+ * per loop pass; starts x', y' as the normalised current shares 100 x / (x + y), 100 y / (x + y);
+ * tests "both SLOs fail: keep the partition" first; lowers the other share instead when a share
+ * would pass 100, never below one step; takes the nearest-rank percentile of the window's
+ * samples; fits by ordinary least squares over the latest `history` (share, latency) points, one
+ * per window, with lambda from the integer grid 0 .. min(x) - 1 (smallest squared error; a larger
+ * lambda must win by more than 1e-12 (1 + error)); and uses Eq. 1 alone (b = 0, lambda = 0,
+ * a = latency * share of the latest point) while all points of a phase sit at one share.
+ */
+typedef struct spd_ctrl spd_ctrl;
+typedef struct spd_ctrl_config {
+  double slo_ttft;      /* S^p: TTFT objective, any time unit (the unit of the observations)     */
+  double slo_tpot;      /* S^d: TPOT objective                                                   */
+  double p_slo;         /* percentile of the objectives, 0 < p <= 100 (the paper uses 90)        */
+  int32_t window_size;  /* adjust every window_size iterations (> 0)                             */
+  int32_t max_step;     /* at most this many steps per adjustment (> 0)                          */
+  int32_t step_size;    /* percentage points per step, 1 .. 50                                   */
+  int32_t history;      /* (share, latency) points kept per phase for the fit (>= 1)             */
+} spd_ctrl_config;
+/* SPD_EINVAL on a null pointer or a field outside the ranges above. */
+int spd_ctrl_create(const spd_ctrl_config* cfg, spd_ctrl** out);
+int spd_ctrl_destroy(spd_ctrl* c);
+/* One observed latency (finite, >= 0) into the current window.  Callable from the prefill and
+ * the decode thread at once. */
+int spd_ctrl_observe_ttft(spd_ctrl* c, double latency);
+int spd_ctrl_observe_tpot(spd_ctrl* c, double latency);
+/* Algorithm 1 for iteration `iter` (>= 0) under the current partition (x0, y0), each within
+ * step_size .. 100: writes the partition to use from now on to *x, *y (equal to x0, y0 when
+ * iter is not a multiple of window_size, when a window is empty, or when nothing has to move).
+ * Closing a window clears its samples. */
+int spd_ctrl_step(spd_ctrl* c, int64_t iter, int32_t x0, int32_t y0, int32_t* x, int32_t* y);
+/* The current model to host out[5] = {a1, lambda, b1, a2, b2} (zeros before the first window). */
+int spd_ctrl_model(spd_ctrl* c, double* out);
+
 const char* spd_strerror(int status);
 /* The hipError_t of the most recent SPD_EHIP on this thread (0 if none). */
 int spd_last_hip_error(void);

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsemipd.so")
-SOURCES = ["pool.cpp", "ctx.cpp", "steps.cpp", "kernels_kv.hip", "kernels_decode.hip", "kernels_decode_mla.hip",
+SOURCES = ["pool.cpp", "ctx.cpp", "steps.cpp", "controller.cpp", "kernels_kv.hip", "kernels_decode.hip", "kernels_decode_mla.hip",
            "kernels_prefill.hip"]
 # packed fp32 VALU forms are switched off for all device code
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -24,6 +24,8 @@ def build(verbose: bool = False) -> str:
         cmd = [hipcc, "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
                "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
                *DEVICE_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        if src.endswith(".cpp"):
+            cmd.insert(-4, "-ffp-contract=off")   # host arithmetic as written (the adjuster's decisions are compared bit for bit)
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -28,6 +28,7 @@ EXPORTS = [
     "spd_phase_sync", "spd_phase_query", "spd_phase_wait_for", "spd_phase_stream", "spd_phase_last_ms",
     "spd_set_partition", "spd_get_partition", "spd_phase_cu_mask", "spd_partition_masks",
     "spd_phase_probe_cus", "spd_strerror", "spd_last_hip_error", "spd_set_kernel_timing", "spd_phase_kernel_ms", "spd_phase_copy",
+    "spd_ctrl_create", "spd_ctrl_destroy", "spd_ctrl_observe_ttft", "spd_ctrl_observe_tpot", "spd_ctrl_step", "spd_ctrl_model",
 ]
 
 
@@ -44,6 +45,11 @@ class PoolExhausted(SpdError):
 class spd_pool_desc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("page_tokens", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("dim_k", C.c_int32), ("dim_v", C.c_int32), ("num_pages", C.c_int64)]
+
+
+class spd_ctrl_config(C.Structure):
+    _fields_ = [("slo_ttft", C.c_double), ("slo_tpot", C.c_double), ("p_slo", C.c_double), ("window_size", C.c_int32),
+                ("max_step", C.c_int32), ("step_size", C.c_int32), ("history", C.c_int32)]
 
 
 class spd_prefill_batch(C.Structure):
@@ -99,6 +105,12 @@ def _load() -> C.CDLL:
         "spd_phase_copy": [vp, C.c_int, vp, vp, u64],
         "spd_set_kernel_timing": [vp, C.c_int],
         "spd_phase_kernel_ms": [vp, C.c_int, P(C.c_float), i32, P(i32)],
+        "spd_ctrl_create": [P(spd_ctrl_config), P(vp)],
+        "spd_ctrl_destroy": [vp],
+        "spd_ctrl_observe_ttft": [vp, C.c_double],
+        "spd_ctrl_observe_tpot": [vp, C.c_double],
+        "spd_ctrl_step": [vp, i64, i32, i32, P(i32), P(i32)],
+        "spd_ctrl_model": [vp, P(C.c_double)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -208,6 +220,38 @@ class Context:
         n = C.c_int32()
         _check(lib.spd_phase_probe_cus(self.h, phase, n_blocks, ids, 2048, C.byref(n)), "spd_phase_probe_cus")
         return [int(ids[i]) for i in range(n.value)]
+
+
+class Adjuster:
+    """SLO-aware partition adjuster (spd_ctrl_*): marshalling only."""
+
+    def __init__(self, slo_ttft: float, slo_tpot: float, p_slo: float = 90.0, window_size: int = 100, max_step: int = 4,
+                 step_size: int = 10, history: int = 64):
+        cfg = spd_ctrl_config(slo_ttft, slo_tpot, p_slo, window_size, max_step, step_size, history)
+        h = C.c_void_p()
+        _check(lib.spd_ctrl_create(C.byref(cfg), C.byref(h)), "spd_ctrl_create")
+        self._h = h
+
+    def close(self):
+        if self._h:
+            lib.spd_ctrl_destroy(self._h)
+            self._h = None
+
+    def observe_ttft(self, latency: float):
+        _check(lib.spd_ctrl_observe_ttft(self._h, latency), "spd_ctrl_observe_ttft")
+
+    def observe_tpot(self, latency: float):
+        _check(lib.spd_ctrl_observe_tpot(self._h, latency), "spd_ctrl_observe_tpot")
+
+    def step(self, it: int, x0: int, y0: int):
+        x, y = C.c_int32(), C.c_int32()
+        _check(lib.spd_ctrl_step(self._h, it, x0, y0, C.byref(x), C.byref(y)), "spd_ctrl_step")
+        return x.value, y.value
+
+    def model(self):
+        out = (C.c_double * 5)()
+        _check(lib.spd_ctrl_model(self._h, out), "spd_ctrl_model")
+        return tuple(out)
 
 
 def partition_masks(total_cus: int, granularity: int, prefill_cus: int, decode_cus: int):

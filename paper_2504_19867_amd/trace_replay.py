@@ -39,11 +39,18 @@ def _summary(xs: List[float]) -> Dict[str, Optional[float]]:
 
 def replay(layer, arrival_s, input_len, output_len, num_pages: int, *, split_before=(40, 60), split_after=(60, 40),
            resize_after_requests: Optional[int] = None, max_decode_batch: int = 512, max_prefill_tokens: int = 16384,
-           time_scale: float = 128.0, seed: int = 0, device: int = 0, log_ops: bool = False):
+           time_scale: float = 128.0, seed: int = 0, device: int = 0, log_ops: bool = False,
+           adjuster: Optional[dict] = None):
     """Replay a trace; returns (stats dict, allocator op log, table snapshots, final free list).
 
     The op log lists, in execution order, ("reserve", req, n_tokens) / ("free", req, 0) exactly as
     the library performed them, so an independent allocator can replay it.
+
+    `adjuster` (keyword arguments of semipd.Adjuster, latencies in virtual seconds) replaces the one
+    fixed mid-run resize by the SLO-aware adjusting algorithm (paper, "Dynamic Adjusting Method"):
+    TTFT = virtual time from arrival to the end of the request's first prefill step, TPOT = virtual
+    duration of a decode step, one adjusting iteration per decode step.  stats["adjuster"] then
+    holds the partition history and, with log_ops, the exact observation / decision stream.
     """
     import torch
 
@@ -100,6 +107,11 @@ def replay(layer, arrival_s, input_len, output_len, num_pages: int, *, split_bef
     preemptions = 0
     prompt_len = [int(x) for x in input_len]     # grows when a preempted request is re-prefilled with its output so far
     prefill_cap = 64                             # requests per prefill batch; halved while the pool is short
+    adj = S.Adjuster(**adjuster) if adjuster else None
+    adj_log: List[tuple] = []
+    adj_history: List[tuple] = []                # (decode iteration, x, y, set_partition call ms)
+    share = [int(split_before[0]), int(split_before[1])]
+    first_prefill_done = [False] * n_req
     t0 = time.perf_counter()
     vt_offset = 0.0
 
@@ -119,6 +131,12 @@ def replay(layer, arrival_s, input_len, output_len, num_pages: int, *, split_bef
             pre_ms.append(ms)
             for r in prefill_inflight:
                 ready.append(r)
+                if adj is not None and not first_prefill_done[r]:
+                    first_prefill_done[r] = True
+                    v = max(0.0, vt() - float(arrival_s[r]))
+                    adj.observe_ttft(v)
+                    if log_ops:
+                        adj_log.append(("ttft", v))
             prefill_inflight = None
             progressed = True
         if prefill_inflight is None and waiting:
@@ -164,6 +182,18 @@ def replay(layer, arrival_s, input_len, output_len, num_pages: int, *, split_bef
             running = still
             decode_inflight = None
             progressed = True
+            if adj is not None:
+                v = ms * 1e-3 * time_scale
+                adj.observe_tpot(v)
+                x, y = adj.step(len(dec_ms), share[0], share[1])
+                if log_ops:
+                    adj_log.append(("tpot", v))
+                    adj_log.append(("step", len(dec_ms), share[0], share[1], x, y))
+                if (x, y) != (share[0], share[1]):
+                    t1 = time.perf_counter()
+                    ctx.set_partition(cus(x), cus(y))         # delayed + asynchronous: adopted at each phase's next step
+                    adj_history.append((len(dec_ms), x, y, (time.perf_counter() - t1) * 1e3))
+                    share = [x, y]
         if decode_inflight is None:
             while ready and len(running) < max_decode_batch:
                 running.append(ready.popleft())
@@ -195,7 +225,7 @@ def replay(layer, arrival_s, input_len, output_len, num_pages: int, *, split_bef
                     progressed = True
 
         # ---- controller: one resize, delayed + asynchronous (each phase adopts at its next step)
-        if resized_at_step is None and finished + len(running) + len(ready) >= resize_after_requests and next_arrival >= resize_after_requests:
+        if adj is None and resized_at_step is None and finished + len(running) + len(ready) >= resize_after_requests and next_arrival >= resize_after_requests:
             t1 = time.perf_counter()
             ctx.set_partition(cus(split_after[0]), cus(split_after[1]))
             resize_call_ms = (time.perf_counter() - t1) * 1e3
@@ -236,6 +266,14 @@ def replay(layer, arrival_s, input_len, output_len, num_pages: int, *, split_bef
         "pool": {"pages": num_pages, "peak_used_pages": peak_used, "exhausted_events": exhausted_events, "preemptions": preemptions,
                  "final": pool.stats()},
     }
+    if adj is not None:
+        stats["adjuster"] = {"config": dict(adjuster), "start": [int(split_before[0]), int(split_before[1])],
+                             "adjustments": len(adj_history), "history": [list(h) for h in adj_history], "final_share": share,
+                             "model_a1_lambda_b1_a2_b2": list(adj.model()),
+                             "set_partition_call_ms": _summary([h[3] for h in adj_history])}
+        if log_ops:
+            stats["adjuster"]["log"] = adj_log
+        adj.close()
     free_list = pool.kv_free_list() if log_ops else None
     out_finite = bool(torch.isfinite(dout.float()).all().item())
     stats["decode_outputs_finite"] = out_finite
@@ -256,13 +294,19 @@ def main():
     ap.add_argument("--rate", type=float, default=8.0)
     ap.add_argument("--pool-frac", type=float, default=0.8, help="fraction of HBM given to the unified pool")
     ap.add_argument("--time-scale", type=float, default=128.0)
+    ap.add_argument("--adjust", action="store_true", help="run the SLO-aware adjusting algorithm instead of one fixed resize")
+    ap.add_argument("--slo-ttft", type=float, default=0.5, help="TTFT objective, virtual seconds")
+    ap.add_argument("--slo-tpot", type=float, default=0.05, help="TPOT objective, virtual seconds")
+    ap.add_argument("--window", type=int, default=100)
     args = ap.parse_args()
     import torch
     layer = W.get_config("c2").layer
     tr = W.trace(args.requests, args.rate)
     hbm = torch.cuda.get_device_properties(0).total_memory
     num_pages = int(args.pool_frac * hbm) // layer.page_bytes
-    stats, _, _, _ = replay(layer, tr.arrival_s, tr.input_len, tr.output_len, num_pages, time_scale=args.time_scale)
+    adjuster = dict(slo_ttft=args.slo_ttft, slo_tpot=args.slo_tpot, p_slo=90.0, window_size=args.window, max_step=4, step_size=10) if args.adjust else None
+    stats, _, _, _ = replay(layer, tr.arrival_s, tr.input_len, tr.output_len, num_pages, time_scale=args.time_scale,
+                            adjuster=adjuster)
     stats["config"] = {"workload": "c5_dynamic_trace", "layer": "Llama-3-8B attention layer", "rate_req_s": args.rate,
                        "pool_bytes": num_pages * layer.page_bytes}
     print(json.dumps(stats))

@@ -35,3 +35,42 @@ def test_reduced_trace_replay_matches_oracle_allocator_and_resizes():
     assert ora.free_stack == free_list
     assert ora.op_seq == stats["pool"]["final"][3] == len(ops)
     assert not ora.tables
+
+
+def test_trace_replay_with_slo_aware_adjuster_decisions_match_oracle():
+    """The adjusting algorithm drives spd_set_partition inside the replay; the oracle, fed the logged
+    observations, must take the same decisions at every iteration (bit-exact integers)."""
+    from oracle import controller as OC
+    layer = W.LayerShape("gqa", 8, 2, 128, 128, 16)
+    tr = W.trace(200, rate_per_s=8.0, seed=78, in_median=96, in_cap=400, out_median=24, out_cap=80)
+    cfg = dict(slo_ttft=0.05, slo_tpot=0.2, p_slo=90.0, window_size=20, max_step=2, step_size=10, history=16)
+    stats, ops, snapshots, free_list = trace_replay.replay(
+        layer, tr.arrival_s, tr.input_len, tr.output_len, 4000, split_before=(30, 70), max_decode_batch=48,
+        max_prefill_tokens=1024, time_scale=2000.0, seed=6, log_ops=True, adjuster=cfg)
+    assert stats["pool"]["final"][1] == 4000 and stats["pool"]["final"][2] == 0
+    assert stats["decode_outputs_finite"]
+    a = stats["adjuster"]
+    ora = OC.Adjuster(**cfg)
+    share = tuple(a["start"])
+    steps = moved = 0
+    for ev in a["log"]:
+        if ev[0] == "ttft":
+            ora.observe_ttft(ev[1])
+        elif ev[0] == "tpot":
+            ora.observe_tpot(ev[1])
+        else:
+            _, it, x0, y0, x, y = ev
+            assert (x0, y0) == share
+            assert ora.step(it, x0, y0) == (x, y), f"iteration {it}"
+            moved += (x, y) != share
+            share = (x, y)
+            steps += 1
+    assert steps == stats["decode_step_ms"]["n"] and moved == a["adjustments"] and list(share) == a["final_share"]
+    # the tight TTFT objective makes the prefill share grow from its small start
+    assert a["adjustments"] >= 1 and a["final_share"][0] > a["start"][0]
+    for g, w in zip(a["model_a1_lambda_b1_a2_b2"], (*ora.model_ttft, *ora.model_tpot)):
+        assert abs(g - w) <= 1e-9 * max(1.0, abs(w))
+    # allocator state still replays exactly
+    alloc = BlockAllocator(4000, layer.page_tokens)
+    alloc.replay(ops)
+    assert alloc.free_stack == free_list and not alloc.tables

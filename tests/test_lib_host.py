@@ -242,3 +242,80 @@ def test_step_argument_validation():
             fn()
         assert e.value.status == S.SPD_EINVAL
     assert pool.stats()[2] == 1
+
+
+# ---------------------------------------------------------------- SLO-aware partition adjuster
+def _feed(adj, ora, ttfts, tpots):
+    for v in ttfts:
+        adj.observe_ttft(v)
+        ora.observe_ttft(v)
+    for v in tpots:
+        adj.observe_tpot(v)
+        ora.observe_tpot(v)
+
+
+def test_adjuster_matches_hand_worked_trace_and_oracle():
+    import os
+    from oracle import controller as OC
+    golden = os.path.join(os.path.dirname(__file__), "golden", "controller_trace.txt")
+    runs = {}
+    for line in open(golden):
+        line = line.split("#")[0].split()
+        if not line:
+            continue
+        run, it, x0, y0, ttft, tpot, x, y = line[0], *[float(v) for v in line[1:]]
+        if run not in runs:
+            runs[run] = (S.Adjuster(100.0, 20.0, 90.0, 1, 4, 10), OC.Adjuster(100.0, 20.0, 90.0, 1, 4, 10))
+        adj, ora = runs[run]
+        _feed(adj, ora, [ttft * 0.5] * 8 + [ttft, ttft * 3], [tpot * 0.5] * 8 + [tpot, tpot * 3])
+        got = adj.step(int(it), int(x0), int(y0))
+        assert got == (int(x), int(y)) == ora.step(int(it), int(x0), int(y0)), f"run {run} window {int(it)}"
+    for adj, _ in runs.values():
+        adj.close()
+
+
+def test_adjuster_decisions_bit_exact_and_model_close_on_random_streams():
+    import random
+    from oracle import controller as OC
+    rnd = random.Random(5)
+    moved = 0
+    for trial in range(150):
+        ss = rnd.choice((5, 10, 20))
+        kw = dict(slo_ttft=rnd.uniform(50, 400), slo_tpot=rnd.uniform(5, 60), p_slo=rnd.choice((50.0, 90.0, 99.0)),
+                  window_size=rnd.choice((1, 3, 8)), max_step=rnd.choice((1, 2, 4)), step_size=ss, history=rnd.choice((2, 8, 64)))
+        adj, ora = S.Adjuster(**kw), OC.Adjuster(**kw)
+        x, y = rnd.choice(range(ss, 101, ss)), rnd.choice(range(ss, 101, ss))
+        # latencies follow a hidden model of the shares plus noise, as a served system's would
+        a1, lam, b1, a2, b2 = rnd.uniform(2e3, 2e4), rnd.uniform(0, 4), rnd.uniform(0, 30), rnd.uniform(200, 3000), rnd.uniform(0, 8)
+        for it in range(60):
+            n = rnd.randint(0, 5)
+            _feed(adj, ora, [max(0.0, a1 / (100.0 * x / (x + y) - lam) + b1 + rnd.gauss(0, 5)) for _ in range(n)],
+                  [max(0.0, a2 / (100.0 * y / (x + y)) + b2 + rnd.gauss(0, 1)) for _ in range(n)])
+            got, want = adj.step(it, x, y), ora.step(it, x, y)
+            assert got == want, f"trial {trial} iter {it}: {got} vs {want}"
+            moved += got != (x, y)
+            x, y = got
+            m = adj.model()
+            for g, w in zip(m, (*ora.model_ttft, *ora.model_tpot)):
+                assert abs(g - w) <= 1e-9 * max(1.0, abs(w)), (m, ora.model_ttft, ora.model_tpot)
+        adj.close()
+    assert moved > 100          # the streams do exercise the adjusting branches
+
+
+def test_adjuster_argument_checks():
+    with pytest.raises(S.SpdError):
+        S.Adjuster(0.0, 20.0)
+    with pytest.raises(S.SpdError):
+        S.Adjuster(100.0, 20.0, p_slo=0.0)
+    with pytest.raises(S.SpdError):
+        S.Adjuster(100.0, 20.0, step_size=60)
+    adj = S.Adjuster(100.0, 20.0, step_size=10)
+    with pytest.raises(S.SpdError):
+        adj.observe_ttft(float("nan"))
+    with pytest.raises(S.SpdError):
+        adj.step(0, 5, 50)          # below one step
+    with pytest.raises(S.SpdError):
+        adj.step(-1, 50, 50)
+    assert adj.step(0, 50, 50) == (50, 50)      # empty window: unchanged
+    assert adj.model() == (0.0, 0.0, 0.0, 0.0, 0.0)
+    adj.close()
