@@ -196,6 +196,21 @@ def test_prefill_ragged_lengths(H, Hkv, d):
     gp.close()
 
 
+@pytest.mark.parametrize("H,Hkv,d", [(16, 2, 128), (8, 1, 64), (32, 2, 128), (6, 2, 128), (12, 2, 64), (5, 1, 128)])
+def test_prefill_head_groupings(H, Hkv, d):
+    """Every way the 8 waves of a workgroup are split over query heads and row sub-tiles: group sizes
+    8 and 16 (8 heads per workgroup), 6 (2 heads), 3 and 5 (1 head: 256 rows per workgroup)."""
+    layer = W.LayerShape("gqa", H, Hkv, d, d, 16)
+    lens = (70, 129, 1, 300, 257, 513)
+    gp = GpuPool(layer, 128, poison=True)
+    (q, k, v, cu, scale), out, ids = run_prefill(gp, lens, seed=31 + H + d)
+    want = OA.prefill_attention(f64(q), f64(k), f64(v), cu, scale)
+    got = host_f64(out)
+    for r in range(len(lens)):
+        assert_parity(got[cu[r]:cu[r + 1]], want[cu[r]:cu[r + 1]], f"prefill H={H} Hkv={Hkv} d={d} len={lens[r]}")
+    gp.close()
+
+
 def test_decode_equals_last_prefill_row_on_gpu():
     layer = W.LayerShape("gqa", 8, 2, 128, 128, 16)
     gp = GpuPool(layer, 64)
@@ -305,4 +320,35 @@ def test_c2_full_size_sampled_against_oracle():
         g = h // (L.n_q_heads // L.n_kv_heads)
         want = OA.causal_attention(qf[a:b, h:h + 1], kf[a:b, g:g + 1], vf[a:b, g:g + 1], scale)
         assert_parity(got[a:b, h:h + 1], want, f"c2 prefill request {r} head {h}")
+    gp.close()
+
+
+def test_c3_full_size_sampled_against_oracle():
+    """Llama-3-70B layer shape (64 query heads over 8 KV heads: 8 heads per prefill workgroup) at the
+    bench's sizes: 8 x 4096 prefill tokens, 128 decode requests; sampled against the oracle."""
+    cfg = W.get_config("c3")
+    L = cfg.layer
+    scale = 1.0 / math.sqrt(L.dim_qk)
+    gp = GpuPool(L, 40960)
+    total, _, _ = gp.ctx.device_info()
+    gp.ctx.set_partition(total // 2, total // 2)
+    for op, r, n in W.scramble_ops(30000, 16, seed=cfg.seed):
+        gp.pool.kv_reserve(r, n) if op == "reserve" else gp.pool.kv_free(r)
+    n_dec = 24                                      # oracle time: the first 24 of the 128 requests
+    qd, ks, vs, dids = fill_decode_contexts(gp, cfg.decode_ctx[:n_dec], cfg.seed + 1)
+    q, k, v, cu = W.prefill_inputs(L, cfg.prefill_lens, cfg.seed)
+    tq, tk, tv, tqd = dev_bf16(q), dev_bf16(k), dev_bf16(v), dev_bf16(qd)
+    op = torch.empty((q.shape[0], L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=DEV)
+    od = torch.empty((len(dids), L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=DEV)
+    gp.pool.prefill_step(list(range(1, len(cfg.prefill_lens) + 1)), cu, tq, tk, tv, op, L.n_q_heads, L.n_kv_heads, L.dim_qk, L.dim_v, scale)
+    gp.pool.decode_step(dids, cfg.decode_ctx[:n_dec], tqd, od, L.n_q_heads, scale)
+    gp.ctx.phase_sync(PRE)
+    gp.ctx.phase_sync(DEC)
+    assert_parity(host_f64(od), oracle_decode(qd, ks, vs, scale), "c3 decode (24 requests)")
+    G = L.n_q_heads // L.n_kv_heads
+    for r, h in [(0, 0), (3, 29), (7, 63)]:
+        a, b = cu[r], cu[r + 1]
+        g = h // G
+        want = OA.causal_attention(f64(q[a:b, h:h + 1]), f64(k[a:b, g:g + 1]), f64(v[a:b, g:g + 1]), scale)
+        assert_parity(host_f64(op[a:b, h:h + 1]), want, f"c3 prefill request {r} head {h}")
     gp.close()
