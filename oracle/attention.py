@@ -73,6 +73,32 @@ def prefill_attention(q, k, v, cu_seqlens, scale: float) -> np.ndarray:
     return out
 
 
+def chunk_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float) -> np.ndarray:
+    """A chunk of a prompt attending to everything before it and causally to itself
+    (paper, Evaluation "Baselines": the chunked-prefill variants process a prompt piece by piece,
+    each piece over the cache built so far).
+
+    q [C,H,dqk] are the chunk's C query rows, k [n,Hkv,dqk], v [n,Hkv,dv] the n = prefix + C rows of
+    the request so far, the chunk's own rows last.  Row i of the chunk sits at position prefix + i:
+        O[i,h] = sum_{j <= prefix+i} softmax_j(scale * Q[i,h].K[j,g]) V[j,g].
+    """
+    q, k, v = (np.asarray(a, dtype=F64) for a in (q, k, v))
+    C, H, _ = q.shape
+    n, Hkv = k.shape[0], k.shape[1]
+    if C == 0 or n < C:
+        raise ValueError("chunk longer than its context, or empty")
+    prefix = n - C
+    group = H // Hkv
+    future = np.arange(n)[None, :] > (prefix + np.arange(C))[:, None]      # j > prefix + i
+    out = np.empty((C, H, v.shape[2]), dtype=F64)
+    for h in range(H):
+        g = h // group
+        s = scale * (q[:, h, :] @ k[:, g, :].T)
+        s[future] = -np.inf
+        out[:, h, :] = _softmax_rows(s) @ v[:, g, :]
+    return out
+
+
 def decode_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float) -> np.ndarray:
     """o[h] = softmax_t(scale * q[h].K[t,g]) V[t,g] over all n cached tokens (no mask).
 

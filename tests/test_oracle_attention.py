@@ -321,3 +321,36 @@ def test_workload_generators_are_seeded_and_shaped():
     assert a[0].shape == (256, 8, 64) and a[0].dtype == np.uint16 and list(a[3]) == [0, 128, 256]
     tr = W.trace(200)
     assert np.all(np.diff(tr.arrival_s) >= 0) and tr.input_len.max() <= 8192 and tr.output_len.min() >= 1
+
+
+# ---------------------------------------------------------------- chunked prefill over a cached prefix
+def test_chunk_attention_is_the_matching_rows_of_causal_attention():
+    """The definition: processing a prompt piece by piece must give the rows that processing it whole gives."""
+    rng = np.random.default_rng(41)
+    L, H, Hkv, d = 53, 4, 2, 16
+    q, k, v = rng.normal(size=(L, H, d)), rng.normal(size=(L, Hkv, d)), rng.normal(size=(L, Hkv, d))
+    whole = A.causal_attention(q, k, v, 0.25)
+    cuts = [0, 1, 17, 18, 40, 53]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        got = A.chunk_attention(q[a:b], k[:b], v[:b], 0.25)
+        np.testing.assert_allclose(got, whole[a:b], rtol=1e-12, atol=1e-14)
+    # no prefix: the chunk is the whole prompt
+    np.testing.assert_allclose(A.chunk_attention(q, k, v, 0.25), whole, rtol=1e-12, atol=1e-14)
+
+
+def test_chunk_attention_brute_force_and_single_row_is_decode():
+    rng = np.random.default_rng(42)
+    n, C, H, Hkv, d = 11, 4, 2, 1, 8
+    q, k, v = rng.normal(size=(C, H, d)), rng.normal(size=(n, Hkv, d)), rng.normal(size=(n, Hkv, d))
+    got = A.chunk_attention(q, k, v, 0.3)
+    for i in range(C):
+        for h in range(H):
+            pos = n - C + i
+            w = [math.exp(0.3 * sum(q[i, h, x] * k[j, 0, x] for x in range(d))) for j in range(pos + 1)]
+            z = sum(w)
+            for x in range(d):
+                assert got[i, h, x] == pytest.approx(sum(w[j] * v[j, 0, x] for j in range(pos + 1)) / z, rel=1e-11, abs=1e-13)
+    # a chunk of one row over its context is the decode step
+    np.testing.assert_allclose(A.chunk_attention(q[-1:], k, v, 0.3)[0], A.decode_attention(q[-1], k, v, 0.3), rtol=1e-12)
+    with pytest.raises(ValueError):
+        A.chunk_attention(q, k[:3], v[:3], 0.3)
