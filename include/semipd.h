@@ -135,7 +135,17 @@ int spd_kv_gather(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int3
  * per-head tensors (n_kv_heads == n_q_heads, dim_qk 192, dim_v 128) and `latent` device
  * [T, 576] is what is written to the pages; latent must be NULL for a GQA pool.
  * Zero-length requests are SPD_EINVAL; scale must be positive and finite (the running maximum
- * of the scores is taken before scaling). */
+ * of the scores is taken before scaling).
+ *
+ * Chunked prefill (paper, Evaluation "Baselines": the chunked-prefill variants): with
+ * prefix_lens non-NULL (GQA pools only) request r already has prefix_lens[r] >= 0 tokens in its
+ * pages and the rows given are the next piece of its prompt, at positions prefix .. prefix+len-1:
+ *     out[i, h, :] = sum_{j <= prefix + i} softmax_j(scale * q[i, h, :] . K_r[j, g, :]) * V_r[j, g, :]
+ * where K_r, V_r are the cached rows followed by the piece's own.  The step reserves blocks for
+ * prefix + len tokens, writes the new rows to the pages, gathers each request's rows
+ * 0 .. prefix+len-1 through its block table into a library workspace and attends over that.  A
+ * request with prefix > 0 must exist with at least prefix tokens reserved (else SPD_ENOENT /
+ * SPD_EINVAL). */
 typedef struct {
   int32_t n_req;
   const uint64_t* req_ids;   /* host [n_req] */
@@ -150,6 +160,7 @@ typedef struct {
   int32_t dim_qk;
   int32_t dim_v;
   float scale;
+  const int32_t* prefix_lens; /* host [n_req] or NULL (no cached prefix) */
 } spd_prefill_batch;
 int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_batch* batch);
 

@@ -71,10 +71,12 @@ struct TileDesc {
 // Prefill work item = one workgroup: one tile of query rows of one request, for a group of query
 // heads that share a KV head.  len == 0 marks a padding item (the workgroup exits at once).
 struct PrefillWork {
-  int32_t row0;      // first packed row of the request
-  int32_t len;       // request length
-  int32_t q_tile;    // tile index inside the request (tile height depends on the head grouping)
+  int32_t row0;      // first packed row of the request's queries (and outputs)
+  int32_t len;       // number of query rows of the request in this step
+  int32_t q_tile;    // tile index inside those rows (tile height depends on the head grouping)
   int32_t head0;     // first query head of the workgroup's head group
+  int32_t kv_row0;   // first row of the request's keys / values in the K, V tensors the kernel reads
+  int32_t q_off;     // position of query row 0 in the request = number of cached tokens before it
 };
 
 extern thread_local int g_last_hip_error;

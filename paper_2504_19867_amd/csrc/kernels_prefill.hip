@@ -4,6 +4,8 @@
 // context.  For request r, query head h (KV head g = h / (H / Hkv)), row i:
 //     out[i,h,:] = sum_{j<=i} softmax_j(scale * q[i,h,:] . k[j,g,:]) * v[j,g,:]
 // (The page write of K, V that belongs to the same step is kv_write_kernel.)
+// With a cached prefix of p tokens (chunked prefill) the request's K, V hold p + len rows and
+// query row i sits at position p + i: the sum runs over j <= p + i.
 //
 // A dense contraction, so it runs on the matrix cores.  One workgroup = 8 waves = one CU's worth
 // of work; every wave owns 32 query rows of one head.  The 8 waves are HB query heads of ONE
@@ -90,6 +92,9 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
   const bool wave_active = wave_q0 < w.len;     // waves past the prompt's end only help loading
   const int qi = wave_q0 + n32;                 // this lane's query (row inside the request)
   const int qi_c = qi < w.len ? qi : w.len - 1;
+  const int kv_len = w.q_off + w.len;           // cached prefix + this step's rows
+  const int pos0 = w.q_off + wave_q0;           // position of this wave's first query in the request
+  const int pos = w.q_off + qi;                 // ... of this lane's query
 
   // Q^T fragments (B operand: column = query, 8 consecutive dims per lane and k-step)
   bf16x8 qf[KS];
@@ -99,10 +104,10 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * s));
   }
 
-  const int kv_end = min(w.len, q_start + 32 * QS);
+  const int kv_end = min(kv_len, w.q_off + q_start + 32 * QS);
   const int n_kv_tiles = (kv_end + BN - 1) / BN;
-  const char* kbase = (const char*)(k + ((size_t)w.row0 * Hkv + g) * DQK);
-  const char* vbase = (const char*)(v + ((size_t)w.row0 * Hkv + g) * DV);
+  const char* kbase = (const char*)(k + ((size_t)w.kv_row0 * Hkv + g) * DQK);
+  const char* vbase = (const char*)(v + ((size_t)w.kv_row0 * Hkv + g) * DV);
   const uint32_t k_pitch = (uint32_t)Hkv * DQK * 2, v_pitch = (uint32_t)Hkv * DV * 2;
   const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
 
@@ -137,14 +142,14 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     const uint32_t stage = smem_base + (uint32_t)(kt % NSTAGE) * STAGE_BYTES;
     const char* kb = kbase + (size_t)kv0 * k_pitch;
     const char* vb = vbase + (size_t)kv0 * v_pitch;
-    if (kv0 + BN <= w.len) {
+    if (kv0 + BN <= kv_len) {
 #pragma unroll
       for (int j = 0; j < LPW; ++j) {
         const int ii = wave + WAVES * j;
         dma16s(ii < CHK ? kb : vb, ld_voff[j], stage + (uint32_t)ii * 1024);
       }
     } else {                                    // rows past the prompt re-read its last row
-      const int last = w.len - 1 - kv0;
+      const int last = kv_len - 1 - kv0;
 #pragma unroll
       for (int j = 0; j < LPW; ++j) {
         const int ii = wave + WAVES * j;
@@ -200,7 +205,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     // all waves: tile kt has landed, and everyone is done with tile kt - 1, whose stage is refilled next
     asm volatile("s_barrier" ::: "memory");
     if (kt + PD < n_kv_tiles) issue_loads(kt + PD);
-    if (!wave_active || kv0 > wave_q0 + 31) continue;          // every key of the tile is in this wave's future
+    if (!wave_active || kv0 > pos0 + 31) continue;             // every key of the tile is in this wave's future
 
     const char* stage = smem + (kt % NSTAGE) * STAGE_BYTES;
     auto read_k = [&](int i) -> uint4 { return *(const uint4*)(stage + k_off[i / 2] + (i % 2) * (32 * CHK * 16)); };
@@ -235,13 +240,13 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
       vr[0][blk][1] = read_v(blk, 1);
     }
 
-    // lane holds, for query qi, keys kv0 + 32b + 8*(i/4) + 4*hh + i%4
-    if (kv0 + BN - 1 > wave_q0) {               // tile crosses this wave's diagonal (or the prompt's end)
+    // lane holds, for the query at position pos, keys kv0 + 32b + 8*(i/4) + 4*hh + i%4
+    if (kv0 + BN - 1 > pos0) {               // tile crosses this wave's diagonal (or the prompt's end)
 #pragma unroll
       for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-          if (kv0 + 32 * b + 8 * (i >> 2) + 4 * hh + (i & 3) > qi) S[b][i] = -INFINITY;
+          if (kv0 + 32 * b + 8 * (i >> 2) + 4 * hh + (i & 3) > pos) S[b][i] = -INFINITY;
     }
     float mx = S[0][0];
 #pragma unroll

@@ -100,35 +100,79 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   }
   if (ctx->device < 0) return SPD_ESTATE;
 
+  // chunked prefill: some request continues a prompt whose first prefix_lens[r] tokens are cached
+  bool chunked = false;
+  if (b->prefix_lens) {
+    if (g.kind != SPD_KV_GQA) return SPD_EINVAL;
+    for (int r = 0; r < b->n_req; ++r) {
+      if (b->prefix_lens[r] < 0) return SPD_EINVAL;
+      chunked = chunked || b->prefix_lens[r] > 0;
+    }
+  }
+  // rows of each request in the gathered K, V (prefix + this step's rows)
+  std::vector<int32_t> kv_cu;
+  if (chunked) {
+    kv_cu.resize((size_t)b->n_req + 1, 0);
+    for (int r = 0; r < b->n_req; ++r) {
+      const int64_t rows = (int64_t)kv_cu[(size_t)r] + b->prefix_lens[r] + (b->cu_seqlens[r + 1] - b->cu_seqlens[r]);
+      if (rows > INT32_MAX) return SPD_EINVAL;
+      kv_cu[(size_t)r + 1] = (int32_t)rows;
+    }
+  }
+
   std::vector<PrefillWork> work;
-  build_prefill_work(b->cu_seqlens, b->n_req, b->n_q_heads, b->n_kv_heads, ctx->xcds, work);
+  build_prefill_work(b->cu_seqlens, chunked ? b->prefix_lens : nullptr, chunked ? kv_cu.data() : nullptr, b->n_req,
+                     b->n_q_heads, b->n_kv_heads, ctx->xcds, work);
 
   hipStream_t stream;
   int rc = phase_enter(ctx, SPD_PHASE_PREFILL, &stream);
   if (rc != SPD_OK) return rc;
 
-  size_t n_descs = 0;
-  for (int r = 0; r < b->n_req; ++r) n_descs += (size_t)(b->cu_seqlens[r + 1] - b->cu_seqlens[r] + TILE_T - 1) / TILE_T;
+  size_t n_descs = 0, n_gather = 0;
+  for (int r = 0; r < b->n_req; ++r) {
+    const int32_t len = b->cu_seqlens[r + 1] - b->cu_seqlens[r], pre = chunked ? b->prefix_lens[r] : 0;
+    n_descs += (size_t)((pre % TILE_T) + len + TILE_T - 1) / TILE_T;
+    if (chunked) n_gather += (size_t)(pre + len + TILE_T - 1) / TILE_T;
+  }
   size_t off_desc = align16(work.size() * sizeof(PrefillWork));
-  size_t bytes = off_desc + n_descs * sizeof(TileDesc);
+  size_t off_gather = align16(off_desc + n_descs * sizeof(TileDesc));
+  size_t bytes = off_gather + n_gather * sizeof(TileDesc);
   spd_stage* st;
   if ((rc = stage_acquire(ctx, SPD_PHASE_PREFILL, bytes, &st)) != SPD_OK) return rc;
-  std::vector<TileDesc> descs;
+  char* ws = nullptr;
+  size_t ws_k_bytes = 0;
+  if (chunked) {
+    ws_k_bytes = align16((size_t)kv_cu.back() * g.Hkv * g.dk * 2);
+    const size_t ws_v_bytes = (size_t)kv_cu.back() * g.Hkv * g.dv * 2;
+    if ((rc = workspace_reserve(ctx, SPD_PHASE_PREFILL, ws_k_bytes + ws_v_bytes, &ws)) != SPD_OK) return rc;
+  }
+  std::vector<TileDesc> descs, gdescs;
   descs.reserve(n_descs);
+  gdescs.reserve(n_gather);
   {
     std::lock_guard<std::mutex> lk(pool->mu);                       // atomic: query, get, update
     int64_t need = 0;
-    for (int r = 0; r < b->n_req; ++r)
-      need += blocks_missing_locked(pool, b->req_ids[r], b->cu_seqlens[r + 1] - b->cu_seqlens[r]);
+    for (int r = 0; r < b->n_req; ++r) {
+      const int32_t len = b->cu_seqlens[r + 1] - b->cu_seqlens[r], pre = chunked ? b->prefix_lens[r] : 0;
+      if (pre > 0) {                                                // the cached prefix must be there
+        auto it = pool->tables.find(b->req_ids[r]);
+        if (it == pool->tables.end()) return SPD_ENOENT;
+        if ((int64_t)it->second.size() * g.P < pre) return SPD_EINVAL;
+      }
+      need += blocks_missing_locked(pool, b->req_ids[r], pre + len);
+    }
     if (need > (int64_t)pool->free_stack.size()) return SPD_ENOMEM;
     for (int r = 0; r < b->n_req; ++r) {
-      int32_t row0 = b->cu_seqlens[r], len = b->cu_seqlens[r + 1] - row0;
-      reserve_locked(pool, b->req_ids[r], len);
-      build_tile_descs(g, pool->tables[b->req_ids[r]].data(), 0, len, row0, descs);
+      const int32_t row0 = b->cu_seqlens[r], len = b->cu_seqlens[r + 1] - row0, pre = chunked ? b->prefix_lens[r] : 0;
+      reserve_locked(pool, b->req_ids[r], pre + len);
+      const int32_t* table = pool->tables[b->req_ids[r]].data();
+      build_tile_descs(g, table, pre, len, row0, descs);
+      if (chunked) build_tile_descs(g, table, 0, pre + len, kv_cu[(size_t)r], gdescs);
     }
   }
   memcpy(st->host, work.data(), work.size() * sizeof(PrefillWork));
   memcpy(st->host + off_desc, descs.data(), descs.size() * sizeof(TileDesc));
+  if (chunked) memcpy(st->host + off_gather, gdescs.data(), gdescs.size() * sizeof(TileDesc));
   spd_phase_state& ps = ctx->phase[SPD_PHASE_PREFILL];
   if (ctx->kernel_timing) SPD_HIP(hipEventRecord(ps.ev_start, stream));
   if ((rc = stage_commit(ctx, SPD_PHASE_PREFILL, st, bytes, stream)) != SPD_OK) return rc;
@@ -136,8 +180,16 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   const void* page_src_v = g.kind == SPD_KV_GQA ? b->v : nullptr;
   SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(st->dev + off_desc), (int)descs.size(), page_src_k,
                           page_src_v, stream));
+  const void *att_k = b->k, *att_v = b->v;
+  if (chunked) {
+    // every request's rows 0 .. prefix+len-1, the new ones included, back out of the pages
+    SPD_HIP(launch_kv_gather(g, pool->base, (const TileDesc*)(st->dev + off_gather), (int)gdescs.size(), ws,
+                             ws + ws_k_bytes, stream));
+    att_k = ws;
+    att_v = ws + ws_k_bytes;
+  }
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_PREFILL, 0, stream)) != SPD_OK) return rc;
-  SPD_HIP(launch_prefill(b->q, b->k, b->v, b->out, (const PrefillWork*)st->dev, (int)work.size(), b->n_q_heads,
+  SPD_HIP(launch_prefill(b->q, att_k, att_v, b->out, (const PrefillWork*)st->dev, (int)work.size(), b->n_q_heads,
                          b->n_kv_heads, b->dim_qk, b->dim_v, b->scale, stream));
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_PREFILL, 1, stream)) != SPD_OK) return rc;
   if (ctx->kernel_timing) {

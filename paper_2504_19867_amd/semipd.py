@@ -56,7 +56,8 @@ class spd_prefill_batch(C.Structure):
     _fields_ = [("n_req", C.c_int32), ("req_ids", C.POINTER(C.c_uint64)), ("cu_seqlens", C.POINTER(C.c_int32)),
                 ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p), ("latent", C.c_void_p),
                 ("out", C.c_void_p), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
-                ("dim_qk", C.c_int32), ("dim_v", C.c_int32), ("scale", C.c_float)]
+                ("dim_qk", C.c_int32), ("dim_v", C.c_int32), ("scale", C.c_float),
+                ("prefix_lens", C.POINTER(C.c_int32))]
 
 
 class spd_decode_batch(C.Structure):
@@ -329,23 +330,20 @@ class Pool:
                "spd_kv_gather")
 
     def prefill_step(self, req_ids: Sequence[int], cu_seqlens: Sequence[int], q, k, v, out, n_q_heads: int,
-                     n_kv_heads: int, dim_qk: int, dim_v: int, scale: float, latent=None) -> None:
-        n = len(req_ids)
-        ids = (C.c_uint64 * n)(*req_ids)
-        cu = (C.c_int32 * (n + 1))(*[int(x) for x in cu_seqlens])
-        b = spd_prefill_batch(n, ids, cu, _ptr(q), _ptr(k), _ptr(v), _ptr(latent), _ptr(out), n_q_heads,
-                              n_kv_heads, dim_qk, dim_v, scale)
-        _check(lib.spd_prefill_step(self.ctx.h, self.h, C.byref(b)), "spd_prefill_step")
+                     n_kv_heads: int, dim_qk: int, dim_v: int, scale: float, latent=None, prefix_lens=None) -> None:
+        self.prefill_step_batch(self.make_prefill_batch(req_ids, cu_seqlens, q, k, v, out, n_q_heads, n_kv_heads,
+                                                        dim_qk, dim_v, scale, latent, prefix_lens))
 
     def make_prefill_batch(self, req_ids: Sequence[int], cu_seqlens: Sequence[int], q, k, v, out, n_q_heads: int,
-                           n_kv_heads: int, dim_qk: int, dim_v: int, scale: float, latent=None):
+                           n_kv_heads: int, dim_qk: int, dim_v: int, scale: float, latent=None, prefix_lens=None):
         """Marshal once; the returned object can be passed to prefill_step_batch repeatedly."""
         n = len(req_ids)
         ids = (C.c_uint64 * n)(*req_ids)
         cu = (C.c_int32 * (n + 1))(*[int(x) for x in cu_seqlens])
+        pre = (C.c_int32 * n)(*[int(x) for x in prefix_lens]) if prefix_lens is not None else None
         b = spd_prefill_batch(n, ids, cu, _ptr(q), _ptr(k), _ptr(v), _ptr(latent), _ptr(out), n_q_heads,
-                              n_kv_heads, dim_qk, dim_v, scale)
-        b._keep = (ids, cu, q, k, v, out, latent)
+                              n_kv_heads, dim_qk, dim_v, scale, pre)
+        b._keep = (ids, cu, q, k, v, out, latent, pre)
         return b
 
     def prefill_step_batch(self, batch) -> None:
