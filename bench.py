@@ -222,6 +222,32 @@ class Bench:
         return wall_ms, pk, dk
 
 
+def run_async(bench, steps, timing=False):
+    """The paper's two asynchronous workers: this thread drives `steps` prefill steps back to back while the
+    library's decode worker thread drives decode steps as fast as the decode partition takes them.  Returns wall
+    ms per prefill step (until both partitions have drained), the number of decode steps, the kernel ms lists."""
+    torch = bench.torch
+    bench.sync()
+    bench.ctx.set_kernel_timing(timing)
+    bench.ctx.phase_kernel_ms(PRE); bench.ctx.phase_kernel_ms(DEC)
+    torch.cuda.synchronize()
+    gc.collect()
+    gc.disable()                        # keep the Python driver's collector out of the timed region
+    t0 = time.perf_counter()
+    worker = bench.pool.decode_worker_start(bench.dec_batches)
+    for _ in range(steps):
+        bench.prefill()
+    bench.ctx.phase_sync(PRE)
+    n_dec = bench.pool.decode_worker_stop(worker)
+    bench.ctx.phase_sync(DEC)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    gc.enable()
+    pk, dk = bench.ctx.phase_kernel_ms(PRE), bench.ctx.phase_kernel_ms(DEC)
+    bench.ctx.set_kernel_timing(False)
+    return wall_ms, n_dec, pk, dk
+
+
 def cpu_baseline(cfg, r):
     """The fp64 oracle, as it stands, timed on this host on a bounded sample of the same workload."""
     import numpy as np
@@ -281,16 +307,20 @@ def main():
     def measure_split(pp, dp, steps, warmup, only=None):
         p_cus, d_cus = bench.set_split(pp, dp)
         copy_gbs = bench.copy_ceiling(DEC)
-        if args.decode_per_prefill > 0:
-            r = args.decode_per_prefill
+        if args.decode_per_prefill > 0 or only:
+            # fixed mix in lockstep (profiling aid), or one phase alone
+            r = max(1, args.decode_per_prefill)
             solo_p_k = solo_p_w = solo_d_k = solo_d_w = float("nan")
+            bench.run_concurrent(warmup, r, only)
+            wall_ms, _, _ = bench.run_concurrent(steps, r, only)                       # the timed region: K steps
+            _, pk, dk = bench.run_concurrent(min(steps, 64), r, only, timing=True)     # same steps again, kernels bracketed by events
         else:
             solo_p_k, solo_p_w = bench.time_solo(PRE, max(5, steps // 4))
             solo_d_k, solo_d_w = bench.time_solo(DEC, max(10, steps))
-            r = max(1, round(solo_p_w / solo_d_w))
-        bench.run_concurrent(warmup, r, only)
-        wall_ms, _, _ = bench.run_concurrent(steps, r, only)                       # the timed region: K steps
-        _, pk, dk = bench.run_concurrent(min(steps, 64), r, only, timing=True)     # same steps again, kernels bracketed by events
+            run_async(bench, warmup)
+            wall_ms, n_dec, _, _ = run_async(bench, steps)                              # the timed region: K prefill steps, decode free-running
+            r = n_dec / steps
+            _, _, pk, dk = run_async(bench, min(steps, 64), timing=True)               # again, kernels bracketed by events
         return {"split": f"{pp}/{dp}", "prefill_cus": p_cus, "decode_cus": d_cus, "decode_per_prefill": r,
                 "ms_per_step": wall_ms, "decode_share_copy_gbs": copy_gbs,
                 "prefill_tok_s": bench.T / wall_ms * 1e3 if only != "decode" else 0.0,
@@ -324,7 +354,9 @@ def main():
                    "q_heads": cfg.layer.n_q_heads, "kv_heads": cfg.layer.n_kv_heads, "head_dim": cfg.layer.dim_qk,
                    "page_tokens": cfg.layer.page_tokens, "pool_pages": bench.num_pages,
                    "cu_split": head["split"], "prefill_cus": head["prefill_cus"], "decode_cus": head["decode_cus"],
-                   "step": f"1 prefill step || {r} decode steps", "only": args.only},
+                   "step": (f"1 prefill step || {r} decode steps (lockstep)" if isinstance(r, int) else
+                            f"1 prefill step, the decode worker free-running beside it ({r:.2f} decode steps per prefill step)"),
+                   "only": args.only},
         "prefill_tok_s": head["prefill_tok_s"], "decode_tok_s": head["decode_tok_s"],
         "roofline": {"bound": "mfma", "kernel": f"prefill_kernel<{cfg.layer.dim_qk},{cfg.layer.dim_v}>", "achieved": head["prefill_tflops"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

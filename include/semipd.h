@@ -192,6 +192,20 @@ typedef struct {
 } spd_decode_batch;
 int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* batch);
 
+/* A decode worker inside the library (paper, System Design, "Prefill and Decode Workers": the
+ * decode worker runs its iterations asynchronously beside the prefill worker).  Starts a host
+ * thread that calls spd_decode_step on batches[0], batches[1], ... batches[n_batches-1],
+ * batches[0], ... back to back (each call blocks only when four of its steps are already in
+ * flight) until it is stopped.  The batch descriptors, the arrays they point to and the pool
+ * must stay valid and unchanged until spd_decode_worker_stop returns; no other thread may drive
+ * the decode phase meanwhile.  Stop joins the thread and reports the number of steps it issued
+ * and the first failing status (SPD_OK if none; the worker ends at the first failure).  The
+ * issued steps may still be running on the GPU: use spd_phase_sync to wait for them. */
+typedef struct spd_worker spd_worker;
+int spd_decode_worker_start(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* const* batches, int32_t n_batches,
+                            spd_worker** out);
+int spd_decode_worker_stop(spd_worker* w, int64_t* steps_issued, int* status);
+
 /* Block the calling thread until everything enqueued so far by `phase` has finished. */
 int spd_phase_sync(spd_ctx* ctx, int phase);
 /* *done = 1 if everything enqueued so far by `phase` has finished, else 0.  Never blocks. */

@@ -13,7 +13,9 @@
 
 #include <algorithm>
 #include <new>
+#include <chrono>
 #include <set>
+#include <thread>
 
 using namespace spd;
 
@@ -199,7 +201,11 @@ int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out) {
   spd_phase_state& s = ctx->phase[phase];
   spd_stage& st = s.ring[s.ring_pos];
   if (st.in_flight) {
-    SPD_HIP(hipEventSynchronize(st.done));
+    // Poll, with pauses, instead of hipEventSynchronize: a blocking wait inside the runtime (and a
+    // tight polling loop as well) keeps the other phase's thread from launching meanwhile.
+    hipError_t e;
+    while ((e = hipEventQuery(st.done)) == hipErrorNotReady) std::this_thread::sleep_for(std::chrono::microseconds(20));
+    if (e != hipSuccess) return hip_fail(e);
     st.in_flight = false;
   }
   if (!st.done) SPD_HIP(hipEventCreateWithFlags(&st.done, hipEventDisableTiming));
@@ -220,7 +226,13 @@ int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out) {
 
 int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream) {
   spd_phase_state& s = ctx->phase[phase];
-  SPD_HIP(hipMemcpyAsync(st->dev, st->host, bytes, hipMemcpyHostToDevice, stream));
+  // The step's metadata crosses to the device with a small copy kernel on the phase's own stream
+  // (pinned host memory is device-readable).  hipMemcpyAsync would put it on a copy path that the
+  // two phases share: with each phase driven by its own thread the copies then wait for each
+  // other's predecessors and one phase starves the other.
+  void* host_dev = nullptr;
+  SPD_HIP(hipHostGetDevicePointer(&host_dev, st->host, 0));
+  SPD_HIP(launch_copy(st->dev, host_dev, (bytes + 15) & ~(size_t)15, 1, stream));
   SPD_HIP(hipEventRecord(st->done, stream));
   st->in_flight = true;
   s.ring_pos = (s.ring_pos + 1) % 4;

@@ -8,7 +8,10 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <functional>
+#include <new>
+#include <thread>
 #include <cmath>
 
 using namespace spd;
@@ -363,5 +366,51 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
     SPD_HIP(hipEventRecord(ds.ev_end, stream));
     ds.timed = true;
   }
+  return SPD_OK;
+}
+
+
+// ------------------------------------------------------------------------------------------ decode worker
+struct spd_worker {
+  std::thread th;
+  std::atomic<bool> stop{false};
+  std::atomic<int64_t> issued{0};
+  std::atomic<int> status{SPD_OK};
+};
+
+extern "C" int spd_decode_worker_start(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* const* batches,
+                                       int32_t n_batches, spd_worker** out) {
+  if (!ctx || !pool || pool->ctx != ctx || !batches || n_batches <= 0 || !out) return SPD_EINVAL;
+  for (int i = 0; i < n_batches; ++i)
+    if (!batches[i]) return SPD_EINVAL;
+  if (ctx->device < 0) return SPD_ESTATE;
+  spd_worker* w = new (std::nothrow) spd_worker();
+  if (!w) return SPD_EINVAL;
+  std::vector<const spd_decode_batch*> list(batches, batches + n_batches);
+  w->th = std::thread([w, ctx, pool, list]() {
+    if (hipSetDevice(ctx->device) != hipSuccess) {
+      w->status.store(SPD_EHIP);
+      return;
+    }
+    for (size_t i = 0; !w->stop.load(std::memory_order_relaxed); i = (i + 1) % list.size()) {
+      const int rc = spd_decode_step(ctx, pool, list[i]);
+      if (rc != SPD_OK) {
+        w->status.store(rc);
+        return;
+      }
+      w->issued.fetch_add(1, std::memory_order_relaxed);
+    }
+  });
+  *out = w;
+  return SPD_OK;
+}
+
+extern "C" int spd_decode_worker_stop(spd_worker* w, int64_t* steps_issued, int* status) {
+  if (!w) return SPD_EINVAL;
+  w->stop.store(true);
+  if (w->th.joinable()) w->th.join();
+  if (steps_issued) *steps_issued = w->issued.load();
+  if (status) *status = w->status.load();
+  delete w;
   return SPD_OK;
 }

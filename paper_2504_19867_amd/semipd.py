@@ -28,6 +28,7 @@ EXPORTS = [
     "spd_phase_sync", "spd_phase_query", "spd_phase_wait_for", "spd_phase_stream", "spd_phase_last_ms",
     "spd_set_partition", "spd_get_partition", "spd_phase_cu_mask", "spd_partition_masks",
     "spd_phase_probe_cus", "spd_strerror", "spd_last_hip_error", "spd_set_kernel_timing", "spd_phase_kernel_ms", "spd_phase_copy",
+    "spd_decode_worker_start", "spd_decode_worker_stop",
     "spd_ctrl_create", "spd_ctrl_destroy", "spd_ctrl_observe_ttft", "spd_ctrl_observe_tpot", "spd_ctrl_step", "spd_ctrl_model",
 ]
 
@@ -106,6 +107,8 @@ def _load() -> C.CDLL:
         "spd_phase_copy": [vp, C.c_int, vp, vp, u64],
         "spd_set_kernel_timing": [vp, C.c_int],
         "spd_phase_kernel_ms": [vp, C.c_int, P(C.c_float), i32, P(i32)],
+        "spd_decode_worker_start": [vp, vp, P(P(spd_decode_batch)), i32, P(vp)],
+        "spd_decode_worker_stop": [vp, P(i64), P(C.c_int)],
         "spd_ctrl_create": [P(spd_ctrl_config), P(vp)],
         "spd_ctrl_destroy": [vp],
         "spd_ctrl_observe_ttft": [vp, C.c_double],
@@ -358,6 +361,21 @@ class Pool:
         b = spd_decode_batch(n, ids, lens, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), n_q_heads, scale)
         b._keep = (ids, lens, q, out, k_new, v_new)
         return b
+
+    def decode_worker_start(self, batches):
+        """Start the library's decode worker thread cycling over `batches` (from make_decode_batch); returns a handle."""
+        n = len(batches)
+        arr = (C.POINTER(spd_decode_batch) * n)(*[C.pointer(b) for b in batches])
+        h = C.c_void_p()
+        _check(lib.spd_decode_worker_start(self.ctx.h, self.h, arr, n, C.byref(h)), "spd_decode_worker_start")
+        return (h, arr, list(batches))
+
+    def decode_worker_stop(self, worker) -> int:
+        """Stop and join the worker; returns the number of decode steps it issued (raises on a failed step)."""
+        steps, status = C.c_int64(), C.c_int()
+        _check(lib.spd_decode_worker_stop(worker[0], C.byref(steps), C.byref(status)), "spd_decode_worker_stop")
+        _check(status.value, "decode worker step")
+        return steps.value
 
     def decode_step_batch(self, batch) -> None:
         _check(lib.spd_decode_step(self.ctx.h, self.h, C.byref(batch)), "spd_decode_step")

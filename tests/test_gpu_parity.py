@@ -352,3 +352,40 @@ def test_c3_full_size_sampled_against_oracle():
         want = OA.causal_attention(f64(q[a:b, h:h + 1]), f64(k[a:b, g:g + 1]), f64(v[a:b, g:g + 1]), scale)
         assert_parity(host_f64(op[a:b, h:h + 1]), want, f"c3 prefill request {r} head {h}")
     gp.close()
+
+
+def test_decode_worker_thread_runs_beside_prefill_steps():
+    """The library's decode worker (a host thread of its own) keeps issuing decode steps while this
+    thread drives prefill steps on the other partition; outputs stay the oracle's."""
+    cfg = W.get_config("c1")
+    L = cfg.layer
+    scale = 1.0 / math.sqrt(L.dim_qk)
+    gp = GpuPool(L, cfg.num_pages)
+    total, _, _ = gp.ctx.device_info()
+    gp.ctx.set_partition(total // 2, total // 2)
+    qd, ks, vs, dids = fill_decode_contexts(gp, cfg.decode_ctx, cfg.seed + 1)
+    od = [torch.zeros((len(dids), L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=DEV) for _ in range(2)]
+    tqd = dev_bf16(qd)
+    batches = [gp.pool.make_decode_batch(dids, cfg.decode_ctx, tqd, o, L.n_q_heads, scale) for o in od]
+    q, k, v, cu = W.prefill_inputs(L, cfg.prefill_lens, cfg.seed)
+    tq, tk, tv = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    op = torch.empty((q.shape[0], L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=DEV)
+    pids = list(range(1, len(cfg.prefill_lens) + 1))
+    worker = gp.pool.decode_worker_start(batches)
+    for _ in range(20):
+        gp.pool.prefill_step(pids, cu, tq, tk, tv, op, L.n_q_heads, L.n_kv_heads, L.dim_qk, L.dim_v, scale)
+    gp.ctx.phase_sync(PRE)
+    steps = gp.pool.decode_worker_stop(worker)
+    gp.ctx.phase_sync(DEC)
+    assert steps >= 2
+    want = oracle_decode(qd, ks, vs, scale)
+    for o in od:
+        assert_parity(host_f64(o), want, "decode worker output")
+    assert_parity(host_f64(op), OA.prefill_attention(f64(q), f64(k), f64(v), cu, scale), "prefill beside the decode worker")
+    # a failing step ends the worker and is reported
+    bad = gp.pool.make_decode_batch([987654], [5], tqd, od[0], L.n_q_heads, scale)
+    worker = gp.pool.decode_worker_start([bad])
+    with pytest.raises(S.SpdError) as e:
+        gp.pool.decode_worker_stop(worker)
+    assert e.value.status == S.SPD_ENOENT
+    gp.close()
