@@ -196,7 +196,7 @@ int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* batch)
  * decode worker runs its iterations asynchronously beside the prefill worker).  Starts a host
  * thread that calls spd_decode_step on batches[0], batches[1], ... batches[n_batches-1],
  * batches[0], ... back to back (each call blocks only when four of its steps are already in
- * flight) until it is stopped.  The batch descriptors, the arrays they point to and the pool
+ * flight) until it is stopped, at least once.  The batch descriptors, the arrays they point to and the pool
  * must stay valid and unchanged until spd_decode_worker_stop returns; no other thread may drive
  * the decode phase meanwhile.  Stop joins the thread and reports the number of steps it issued
  * and the first failing status (SPD_OK if none; the worker ends at the first failure).  The

@@ -224,15 +224,22 @@ int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out) {
   return SPD_OK;
 }
 
-int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream) {
+int stage_host_as_device(spd_stage* st, void** out) {
+  SPD_HIP(hipHostGetDevicePointer(out, st->host, 0));
+  return SPD_OK;
+}
+
+int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream, bool copy) {
   spd_phase_state& s = ctx->phase[phase];
   // The step's metadata crosses to the device with a small copy kernel on the phase's own stream
   // (pinned host memory is device-readable).  hipMemcpyAsync would put it on a copy path that the
   // two phases share: with each phase driven by its own thread the copies then wait for each
   // other's predecessors and one phase starves the other.
-  void* host_dev = nullptr;
-  SPD_HIP(hipHostGetDevicePointer(&host_dev, st->host, 0));
-  SPD_HIP(launch_copy(st->dev, host_dev, (bytes + 15) & ~(size_t)15, 1, stream));
+  if (copy) {
+    void* host_dev = nullptr;
+    SPD_HIP(hipHostGetDevicePointer(&host_dev, st->host, 0));
+    SPD_HIP(launch_copy(st->dev, host_dev, (bytes + 15) & ~(size_t)15, 1, stream));
+  }
   SPD_HIP(hipEventRecord(st->done, stream));
   st->in_flight = true;
   s.ring_pos = (s.ring_pos + 1) % 4;

@@ -140,13 +140,18 @@ namespace spd {
 // host helpers (ctx.cpp)
 int phase_enter(spd_ctx* ctx, int phase, hipStream_t* stream_out);   // adopt pending stream
 int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out);
-int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream);
+// copy = false: the caller has already launched a kernel that copies host -> dev (see launch_kv_write)
+int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream, bool copy = true);
+int stage_host_as_device(spd_stage* st, void** out);   // device-readable address of the pinned host buffer
 int workspace_reserve(spd_ctx* ctx, int phase, size_t bytes, char** out);
 int kernel_timing_mark(spd_ctx* ctx, int phase, int which, hipStream_t stream);   // which: 0 begin, 1 end
 
 // kernel launchers (kernels_*.hip); all enqueue on `stream` and return the launch status
+// d_tiles may be device-readable pinned host memory.  With copy_dst non-null the same launch also
+// copies copy_bytes (rounded up to 16) from copy_src to copy_dst.
 hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d_tiles, int n_tiles,
-                           const void* k, const void* v, hipStream_t stream);
+                           const void* k, const void* v, hipStream_t stream, void* copy_dst = nullptr,
+                           const void* copy_src = nullptr, uint64_t copy_bytes = 0);
 hipError_t launch_kv_gather(const PoolGeom& g, const char* pool_base, const TileDesc* d_tiles, int n_tiles,
                             void* k_out, void* v_out, hipStream_t stream);
 hipError_t launch_decode_gqa(const PoolGeom& g, const char* pool_base, const void* q, void* out,

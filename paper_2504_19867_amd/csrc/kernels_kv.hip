@@ -6,17 +6,29 @@
 // (internal.h); they are pure copies, bit-exact.
 #include "internal.h"
 
+#include <algorithm>
+
 namespace spd {
 
 typedef unsigned short bf16_t;
 
-// grid (n_tiles, n_kv_heads), block 256.  One workgroup copies the touched token slots of one
-// 16-token tile of one KV head.
+// grid (n_tiles + copy_cols, n_kv_heads), block 256.  One workgroup copies the touched token slots
+// of one 16-token tile of one KV head.  The descriptors may lie in pinned host memory (one read
+// per workgroup).  Workgroups past n_tiles copy copy_n16 16-byte pieces copy_src -> copy_dst
+// instead: the step's metadata rides along in the same launch.
 __global__ __launch_bounds__(256) void kv_write_kernel(char* __restrict__ base, uint64_t page_bytes,
                                                        uint32_t head_bytes, uint32_t tile_bytes,
                                                        uint32_t tile_k_bytes, const TileDesc* __restrict__ descs,
                                                        const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-                                                       int Hkv, int dk, int dv, int natural) {
+                                                       int Hkv, int dk, int dv, int natural, int n_tiles,
+                                                       uint4* __restrict__ copy_dst, const uint4* __restrict__ copy_src,
+                                                       uint64_t copy_n16) {
+  if ((int)blockIdx.x >= n_tiles) {
+    const uint64_t blk = (uint64_t)(blockIdx.x - n_tiles) * gridDim.y + blockIdx.y;
+    const uint64_t stride = (uint64_t)(gridDim.x - n_tiles) * gridDim.y * blockDim.x;
+    for (uint64_t i = blk * blockDim.x + threadIdx.x; i < copy_n16; i += stride) copy_dst[i] = copy_src[i];
+    return;
+  }
   const TileDesc d = descs[blockIdx.x];
   const int g = blockIdx.y;
   char* tile = base + (uint64_t)d.page * page_bytes + (uint64_t)g * head_bytes + (uint64_t)d.sub * tile_bytes;
@@ -116,11 +128,13 @@ hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, int cus, hipS
 }
 
 hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d_tiles, int n_tiles, const void* k,
-                           const void* v, hipStream_t stream) {
-  if (n_tiles <= 0) return hipSuccess;
-  hipLaunchKernelGGL(kv_write_kernel, dim3(n_tiles, g.Hkv), dim3(256), 0, stream, pool_base, g.page_bytes, g.head_bytes,
-                     g.tile_bytes, g.tile_k_bytes, d_tiles, (const bf16_t*)k, (const bf16_t*)v, g.Hkv, g.dk, g.dv,
-                     g.kind == SPD_KV_MLA_LATENT ? 1 : 0);
+                           const void* v, hipStream_t stream, void* copy_dst, const void* copy_src, uint64_t copy_bytes) {
+  const uint64_t n16 = copy_dst ? (copy_bytes + 15) / 16 : 0;
+  const int copy_cols = n16 ? (int)std::min<uint64_t>(16, (n16 + 256ull * g.Hkv - 1) / (256ull * g.Hkv)) : 0;
+  if (n_tiles <= 0 && copy_cols == 0) return hipSuccess;
+  hipLaunchKernelGGL(kv_write_kernel, dim3(n_tiles + copy_cols, g.Hkv), dim3(256), 0, stream, pool_base, g.page_bytes,
+                     g.head_bytes, g.tile_bytes, g.tile_k_bytes, d_tiles, (const bf16_t*)k, (const bf16_t*)v, g.Hkv, g.dk,
+                     g.dv, g.kind == SPD_KV_MLA_LATENT ? 1 : 0, n_tiles, (uint4*)copy_dst, (const uint4*)copy_src, n16);
   return hipGetLastError();
 }
 

@@ -178,11 +178,16 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   if (chunked) memcpy(st->host + off_gather, gdescs.data(), gdescs.size() * sizeof(TileDesc));
   spd_phase_state& ps = ctx->phase[SPD_PHASE_PREFILL];
   if (ctx->kernel_timing) SPD_HIP(hipEventRecord(ps.ev_start, stream));
-  if ((rc = stage_commit(ctx, SPD_PHASE_PREFILL, st, bytes, stream)) != SPD_OK) return rc;
   const void* page_src_k = g.kind == SPD_KV_GQA ? b->k : b->latent;
   const void* page_src_v = g.kind == SPD_KV_GQA ? b->v : nullptr;
-  SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(st->dev + off_desc), (int)descs.size(), page_src_k,
-                          page_src_v, stream));
+  // one launch: the page write reads its descriptors straight out of the pinned staging buffer,
+  // and extra workgroups of the same kernel copy the whole staging buffer to its device twin,
+  // where the attention kernel (and the gather of a chunked step) find their lists
+  void* host_dev = nullptr;
+  if ((rc = stage_host_as_device(st, &host_dev)) != SPD_OK) return rc;
+  SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)((const char*)host_dev + off_desc), (int)descs.size(), page_src_k,
+                          page_src_v, stream, st->dev, host_dev, bytes));
+  if ((rc = stage_commit(ctx, SPD_PHASE_PREFILL, st, bytes, stream, false)) != SPD_OK) return rc;
   const void *att_k = b->k, *att_v = b->v;
   if (chunked) {
     // every request's rows 0 .. prefix+len-1, the new ones included, back out of the pages
@@ -392,14 +397,16 @@ extern "C" int spd_decode_worker_start(spd_ctx* ctx, spd_pool* pool, const spd_d
       w->status.store(SPD_EHIP);
       return;
     }
-    for (size_t i = 0; !w->stop.load(std::memory_order_relaxed); i = (i + 1) % list.size()) {
+    size_t i = 0;
+    do {                                          // at least one step, however early the stop comes
       const int rc = spd_decode_step(ctx, pool, list[i]);
       if (rc != SPD_OK) {
         w->status.store(rc);
         return;
       }
       w->issued.fetch_add(1, std::memory_order_relaxed);
-    }
+      i = (i + 1) % list.size();
+    } while (!w->stop.load(std::memory_order_relaxed));
   });
   *out = w;
   return SPD_OK;
