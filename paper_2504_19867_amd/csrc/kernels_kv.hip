@@ -44,8 +44,17 @@ __global__ __launch_bounds__(256) void kv_write_kernel(char* __restrict__ base, 
     }
   }
   if (v == nullptr) return;
-  // V part: [d/32][token quad][d%16][(d/16)%2][4 tokens], one 16-byte piece per (d/32, quad, d%16)
+  // V part: [d/32][token quad][d%16][(d/16)%2][4 tokens], one 16-byte piece per (d/32, quad, d%16).
+  // The tile's rows go through LDS (16-byte loads of 8 dims, [token][dim]) and come out transposed.
+  __shared__ bf16_t vs[TILE_T][256 + 8];            // dv <= 256; 8 elements of padding per row
   bf16_t* vt = (bf16_t*)(tile + tile_k_bytes);
+  const int pieces = (dv >> 3) * TILE_T;
+  for (int i = threadIdx.x; i < pieces; i += blockDim.x) {
+    const int t = i / (dv >> 3), c = i % (dv >> 3);
+    if (t >= d.t_begin && t < d.t_end)
+      *(uint4*)&vs[t][c * 8] = *(const uint4*)(v + ((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dv + c * 8);
+  }
+  __syncthreads();
   const int v_items = (dv >> 5) * 64;
   for (int i = threadIdx.x; i < v_items; i += blockDim.x) {
     const int m = i & 15, c4 = (i >> 4) & 3, blk2 = i >> 6;
@@ -58,7 +67,7 @@ __global__ __launch_bounds__(256) void kv_write_kernel(char* __restrict__ base, 
         const int t = 4 * c4 + tt, dd = 32 * blk2 + 16 * par + m;
         const bool ok = t >= d.t_begin && t < d.t_end;
         all = all && ok;
-        vals[par * 4 + tt] = ok ? v[((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dv + dd] : (bf16_t)0;
+        vals[par * 4 + tt] = ok ? vs[t][dd] : (bf16_t)0;
       }
     bf16_t* dst = vt + ((size_t)((blk2 * 4 + c4) * 16 + m) << 3);
     if (all) {
