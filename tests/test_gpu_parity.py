@@ -389,3 +389,38 @@ def test_decode_worker_thread_runs_beside_prefill_steps():
         gp.pool.decode_worker_stop(worker)
     assert e.value.status == S.SPD_ENOENT
     gp.close()
+
+
+def test_long_context_decode_and_long_prompt_prefill():
+    """The largest sizes the workloads name: a 131 072-token context (Llama-3.1's limit) decoded with
+    split-K over ~8000 pages, and a 32 768-token prompt prefilled; sampled against the oracle."""
+    layer = W.LayerShape("gqa", 8, 2, 128, 128, 16)
+    scale = 1.0 / math.sqrt(128)
+    n = 131072
+    gp = GpuPool(layer, n // 16 + 2048 + 64)
+    rng = np.random.default_rng(77)
+    k = W.normal_bf16(rng, (n, 2, 128))
+    v = W.normal_bf16(rng, (n, 2, 128))
+    qd = W.normal_bf16(rng, (2, 8, 128))
+    gp.pool.kv_reserve(1, n)
+    gp.pool.kv_reserve(2, 1)                       # a one-token context beside the long one
+    for a in range(0, n, 32768):                   # written in four pieces
+        gp.pool.kv_write(DEC, 1, a, 32768, dev_bf16(k[a:a + 32768]), dev_bf16(v[a:a + 32768]))
+    gp.pool.kv_write(DEC, 2, 0, 1, dev_bf16(k[:1]), dev_bf16(v[:1]))
+    od = torch.empty((2, 8, 128), dtype=torch.bfloat16, device=DEV)
+    gp.pool.decode_step([1, 2], [n, 1], dev_bf16(qd), od, 8, scale)
+    gp.ctx.phase_sync(DEC)
+    want = np.stack([OA.decode_attention(f64(qd[0]), f64(k), f64(v), scale), OA.decode_attention(f64(qd[1]), f64(k[:1]), f64(v[:1]), scale)])
+    assert_parity(host_f64(od), want, "decode over 131072 tokens")
+    gp.pool.kv_free(1)
+    # 32768-token prompt: rows sampled through the decode oracle (row i attends to rows 0..i)
+    L = 32768
+    q = W.normal_bf16(rng, (L, 8, 128))
+    out = torch.empty((L, 8, 128), dtype=torch.bfloat16, device=DEV)
+    gp.pool.prefill_step([3], [0, L], dev_bf16(q), dev_bf16(k[:L]), dev_bf16(v[:L]), out, 8, 2, 128, 128, scale)
+    gp.ctx.phase_sync(PRE)
+    got = host_f64(out)
+    for i in (0, 63, 64, 4095, 16384, 32767):
+        want_i = OA.decode_attention(f64(q[i]), f64(k[:i + 1]), f64(v[:i + 1]), scale)
+        assert_parity(got[i], want_i, f"prefill row {i} of 32768")
+    gp.close()
