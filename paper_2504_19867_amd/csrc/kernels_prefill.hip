@@ -27,6 +27,7 @@
 // by the LDS transpose read ds_read_b64_tr_b16.  Both tiles are XOR-swizzled at 16-byte
 // granularity against bank conflicts.
 #include "internal.h"
+#include <type_traits>
 
 namespace spd {
 
@@ -178,6 +179,22 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     v_off[blk] = K_BYTES + v_row * (CHV * 16) + (((dim >> 3) ^ v_swz<DV>(v_row)) * 16) + (dim & 7) * 2;
   }
 
+  // The tile loop is unrolled over the ring's stages so that the stage offset is part of each LDS
+  // read's 16-bit immediate; stages 2 and 3 lie beyond its reach and get a second set of lane addresses.
+  constexpr bool UNROLL = NSTAGE == 4 && 2 * STAGE_BYTES <= 65536;
+  int k_off2[KS], v_off2[VB];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    k_off2[ks] = k_off[ks] + 2 * STAGE_BYTES;
+    asm volatile("" : "+v"(k_off2[ks]));        // a value of its own, not "k_off + constant" to be recomputed
+  }
+#pragma unroll
+  for (int blk = 0; blk < VB; ++blk) {
+    v_off2[blk] = v_off[blk] + 2 * STAGE_BYTES;
+    asm volatile("" : "+v"(v_off2[blk]));
+  }
+  const uint32_t ones2 = 0x3f803f80u;           // (1.0, 1.0) in bf16
+
   f32x16 O[VB];
 #pragma unroll
   for (int i = 0; i < VB; ++i)
@@ -195,7 +212,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
 #pragma unroll
   for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(__builtin_bit_cast(uint4, qf[s]).x));
 
-  for (int kt = 0; kt < n_kv_tiles; ++kt) {
+  auto tile = [&](auto stc, int kt) {
+    const int ST = stc;                         // ring stage of tile kt: a constant when the loop is unrolled
     const int kv0 = kt * BN;
     // this wave's loads of tile kt are done when at most (tiles issued after kt) * LPW remain
     const int later = min(PD - 1, n_kv_tiles - 1 - kt);
@@ -205,14 +223,16 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     // all waves: tile kt has landed, and everyone is done with tile kt - 1, whose stage is refilled next
     asm volatile("s_barrier" ::: "memory");
     if (kt + PD < n_kv_tiles) issue_loads(kt + PD);
-    if (!wave_active || kv0 > pos0 + 31) continue;             // every key of the tile is in this wave's future
+    if (!wave_active || kv0 > pos0 + 31) return;               // every key of the tile is in this wave's future
 
-    const char* stage = smem + (kt % NSTAGE) * STAGE_BYTES;
-    auto read_k = [&](int i) -> uint4 { return *(const uint4*)(stage + k_off[i / 2] + (i % 2) * (32 * CHK * 16)); };
+    const char* sbase = UNROLL ? smem + (ST & 1) * STAGE_BYTES : smem + ST * STAGE_BYTES;
+    auto read_k = [&](int i) -> uint4 {
+      return *(const uint4*)(sbase + (UNROLL && ST >= 2 ? k_off2[i / 2] : k_off[i / 2]) + (i % 2) * (32 * CHK * 16));
+    };
     auto read_v = [&](int i, int half) -> s16x4 {
       const int kk = i / VB, blk = i % VB;
-      return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4*)(stage + v_off[blk] + (16 * kk + 8 * half) * (CHV * 16)));
+      return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(
+          sbase + (UNROLL && ST >= 2 ? v_off2[blk] : v_off[blk]) + (16 * kk + 8 * half) * (CHV * 16)));
     };
 
     // ---- S^T = K . Q^T.  Operand i: block b = i % 2 (32 keys), k-step ks = i / 2; LDS reads run
@@ -263,17 +283,21 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     }
     const float m_new = fmaxf(m, mx);
     const float mc = m_new * c;
-    float psum = 0.f;
     uint32_t pb[2][8];
+    float ls[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
         const float p0 = __builtin_amdgcn_exp2f(S[b][i] * c - mc);
         const float p1 = __builtin_amdgcn_exp2f(S[b][i + 1] * c - mc);
-        psum += p0 + p1;
         pb[b][i >> 1] = cvt_pk_bf16(p0, p1);
+        // the row sum runs over the rounded values, the ones the second product multiplies: two per
+        // instruction (the compiler places the wait states that a dot product's result needs)
+        ls[(i >> 1) & 3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pb[b][i >> 1]),
+                                                           __builtin_bit_cast(bf16x2, ones2), ls[(i >> 1) & 3], false);
       }
+    const float psum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
     // the running maximum rarely moves after the first tiles: rescale only when some lane needs it
     if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
       const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
@@ -306,6 +330,24 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+  };
+  if constexpr (UNROLL) {
+    using C0 = std::integral_constant<int, 0>;
+    using C1 = std::integral_constant<int, 1>;
+    using C2 = std::integral_constant<int, 2>;
+    using C3 = std::integral_constant<int, 3>;
+    int kt = 0;
+    for (; kt + 4 <= n_kv_tiles; kt += 4) {
+      tile(C0{}, kt);
+      tile(C1{}, kt + 1);
+      tile(C2{}, kt + 2);
+      tile(C3{}, kt + 3);
+    }
+    if (kt < n_kv_tiles) tile(C0{}, kt);
+    if (kt + 1 < n_kv_tiles) tile(C1{}, kt + 1);
+    if (kt + 2 < n_kv_tiles) tile(C2{}, kt + 2);
+  } else {
+    for (int kt = 0; kt < n_kv_tiles; ++kt) tile(kt % NSTAGE, kt);
   }
 
   l += __shfl_xor(l, 32);

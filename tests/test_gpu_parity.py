@@ -1,6 +1,7 @@
 """GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
 seeded inputs.  Bar: max abs <= 2e-2 and mean abs <= 2e-3 on bf16 outputs; page contents,
 block tables and allocator state bit-exact."""
+import time
 import math
 
 import numpy as np
@@ -372,8 +373,11 @@ def test_decode_worker_thread_runs_beside_prefill_steps():
     op = torch.empty((q.shape[0], L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=DEV)
     pids = list(range(1, len(cfg.prefill_lens) + 1))
     worker = gp.pool.decode_worker_start(batches)
-    for _ in range(20):
+    t_end = time.monotonic() + 0.2              # long enough for the worker thread to get several steps in
+    n_prefill = 0
+    while n_prefill < 20 or time.monotonic() < t_end:
         gp.pool.prefill_step(pids, cu, tq, tk, tv, op, L.n_q_heads, L.n_kv_heads, L.dim_qk, L.dim_v, scale)
+        n_prefill += 1
     gp.ctx.phase_sync(PRE)
     steps = gp.pool.decode_worker_stop(worker)
     gp.ctx.phase_sync(DEC)
