@@ -192,6 +192,42 @@ typedef struct {
 } spd_decode_batch;
 int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* batch);
 
+/* ------------------------------------------------------------------ the step before attention */
+
+/* Rotary position embedding (paper, Evaluation, "Implementation based on DistServe": the RoPE
+ * kernel, modified for the Llama-3.1 models).  The paper gives no formula; this is the published
+ * definition.  Every head vector x of a token at position p is rotated pairwise, pair i
+ * (0 <= i < rotary_dim / 2) by the angle p * w_i:
+ *     x'_a = x_a cos(p w_i) - x_b sin(p w_i),    x'_b = x_b cos(p w_i) + x_a sin(p w_i)
+ * with (a, b) = (off + i, off + i + rotary_dim / 2), or (off + 2i, off + 2i + 1) if `interleaved`,
+ * off = rotary_offset; the other entries of the head pass through.  w_i = theta^(-2i / rotary_dim);
+ * with factor != 1 the Llama-3.1 scaling is applied to it: with wavelength L = 2 pi / w_i,
+ *     L < original_max_pos / high_freq_factor : unchanged
+ *     L > original_max_pos / low_freq_factor  : w_i / factor
+ *     otherwise: s = (original_max_pos / L - low_freq_factor) / (high_freq_factor - low_freq_factor),
+ *                w_i' = (1 - s) w_i / factor + s w_i.
+ * Angles are formed in fp64, the rotation in fp32, the result rounded to bf16 (nearest even). */
+typedef struct {
+  double theta;             /* > 0, e.g. 500000 (Llama-3) */
+  double factor;            /* >= 1; 1 = no frequency scaling (the three fields below are then unused) */
+  double low_freq_factor;   /* > 0 */
+  double high_freq_factor;  /* > low_freq_factor */
+  int32_t original_max_pos; /* > 0 */
+  int32_t rotary_dim;       /* rotating entries per head: positive, a multiple of 16 for spd_rope_qk */
+  int32_t rotary_offset;    /* first rotating entry of a head: >= 0, a multiple of 8 for spd_rope_qk */
+  int32_t interleaved;      /* 0: pairs (i, i + rotary_dim/2); else pairs (2i, 2i + 1) */
+} spd_rope_config;
+/* Host only: writes the rotary_dim / 2 frequencies w_i (scaled if factor != 1) to out[0 .. cap). */
+int spd_rope_inv_freq(const spd_rope_config* cfg, double* out, int32_t cap);
+/* Rotates, in place, q device [n_tokens, n_q_heads, dim] and k device [n_tokens, n_kv_heads, dim]
+ * (bf16, 16-byte aligned; either may be NULL), token t by positions[t] (host [n_tokens], >= 0).
+ * dim must be a multiple of 8 and rotary_offset + rotary_dim <= dim.  Enqueued on `phase`'s current
+ * stream, i.e. on that phase's compute units, before the step that consumes q and k (for a decode
+ * step the new token's position is ctx_len - 1; k_new goes to the pages rotated).  The positions
+ * are copied before the call returns.  SPD_EINVAL on any violated condition, nothing enqueued. */
+int spd_rope_qk(spd_ctx* ctx, int phase, const spd_rope_config* cfg, const int32_t* positions, int32_t n_tokens,
+                void* q, int32_t n_q_heads, void* k, int32_t n_kv_heads, int32_t dim);
+
 /* A decode worker inside the library (paper, System Design, "Prefill and Decode Workers": the
  * decode worker runs its iterations asynchronously beside the prefill worker).  Starts a host
  * thread that calls spd_decode_step on batches[0], batches[1], ... batches[n_batches-1],

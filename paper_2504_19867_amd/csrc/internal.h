@@ -165,6 +165,9 @@ hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const voi
 int decode_mla_step_tokens();
 hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out, const PrefillWork* d_work,
                           int n_work, int H, int Hkv, int dqk, int dv, float scale, hipStream_t stream);
+// d_pos, d_w may be device-readable pinned host memory
+hipError_t launch_rope(void* q, int n_q_heads, void* k, int n_kv_heads, int dim, int rot, int off, bool interleaved,
+                       int n_tokens, const int32_t* d_pos, const double* d_w, hipStream_t stream);
 hipError_t launch_probe(int32_t* d_ids, int n_blocks, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, int cus, hipStream_t stream);
 bool prefill_shape_supported(int dqk, int dv);

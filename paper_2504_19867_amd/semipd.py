@@ -30,6 +30,7 @@ EXPORTS = [
     "spd_phase_probe_cus", "spd_strerror", "spd_last_hip_error", "spd_set_kernel_timing", "spd_phase_kernel_ms", "spd_phase_copy",
     "spd_decode_worker_start", "spd_decode_worker_stop",
     "spd_ctrl_create", "spd_ctrl_destroy", "spd_ctrl_observe_ttft", "spd_ctrl_observe_tpot", "spd_ctrl_step", "spd_ctrl_model",
+    "spd_rope_inv_freq", "spd_rope_qk",
 ]
 
 
@@ -51,6 +52,12 @@ class spd_pool_desc(C.Structure):
 class spd_ctrl_config(C.Structure):
     _fields_ = [("slo_ttft", C.c_double), ("slo_tpot", C.c_double), ("p_slo", C.c_double), ("window_size", C.c_int32),
                 ("max_step", C.c_int32), ("step_size", C.c_int32), ("history", C.c_int32)]
+
+
+class spd_rope_config(C.Structure):
+    _fields_ = [("theta", C.c_double), ("factor", C.c_double), ("low_freq_factor", C.c_double),
+                ("high_freq_factor", C.c_double), ("original_max_pos", C.c_int32), ("rotary_dim", C.c_int32),
+                ("rotary_offset", C.c_int32), ("interleaved", C.c_int32)]
 
 
 class spd_prefill_batch(C.Structure):
@@ -115,6 +122,8 @@ def _load() -> C.CDLL:
         "spd_ctrl_observe_tpot": [vp, C.c_double],
         "spd_ctrl_step": [vp, i64, i32, i32, P(i32), P(i32)],
         "spd_ctrl_model": [vp, P(C.c_double)],
+        "spd_rope_inv_freq": [P(spd_rope_config), P(C.c_double), i32],
+        "spd_rope_qk": [vp, C.c_int, P(spd_rope_config), P(i32), i32, vp, i32, vp, i32, i32],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -150,6 +159,20 @@ def _ptr(x) -> Optional[int]:
     if hasattr(x, "data_ptr"):
         return x.data_ptr()
     return int(x)
+
+
+def rope_config(theta: float = 500000.0, factor: float = 1.0, low_freq_factor: float = 1.0, high_freq_factor: float = 4.0,
+                original_max_pos: int = 8192, rotary_dim: int = 128, rotary_offset: int = 0,
+                interleaved: bool = False) -> spd_rope_config:
+    return spd_rope_config(theta, factor, low_freq_factor, high_freq_factor, original_max_pos, rotary_dim, rotary_offset,
+                           int(interleaved))
+
+
+def rope_inv_freq(cfg: spd_rope_config) -> List[float]:
+    n = max(cfg.rotary_dim // 2, 1)
+    buf = (C.c_double * n)()
+    _check(lib.spd_rope_inv_freq(C.byref(cfg), buf, n), "spd_rope_inv_freq")
+    return [float(buf[i]) for i in range(cfg.rotary_dim // 2)]
 
 
 # ----------------------------------------------------------------------------- thin object wrappers
@@ -209,6 +232,13 @@ class Context:
 
     def phase_copy(self, phase: int, dst, src, nbytes: int) -> None:
         _check(lib.spd_phase_copy(self.h, phase, _ptr(dst), _ptr(src), nbytes), "spd_phase_copy")
+
+    def rope_qk(self, phase: int, cfg: "spd_rope_config", positions: Sequence[int], q, n_q_heads: int, k, n_kv_heads: int,
+                dim: int) -> None:
+        """In-place rotary embedding of q [T, n_q_heads, dim] and k [T, n_kv_heads, dim] on `phase`'s stream."""
+        n = len(positions)
+        pos = (C.c_int32 * max(n, 1))(*positions)
+        _check(lib.spd_rope_qk(self.h, phase, C.byref(cfg), pos, n, _ptr(q), n_q_heads, _ptr(k), n_kv_heads, dim), "spd_rope_qk")
 
     def set_kernel_timing(self, on: bool) -> None:
         _check(lib.spd_set_kernel_timing(self.h, int(on)), "spd_set_kernel_timing")

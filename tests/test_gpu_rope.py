@@ -1,0 +1,144 @@
+"""GPU parity of the rotary-embedding step (C-ABI spd_rope_qk) against the fp64 oracle.
+
+Paper, Evaluation "Implementation based on DistServe": the RoPE kernel, modified for Llama-3.1.
+Bar: the kernel rounds the rotated value to bf16 (nearest even): half an ulp is at most 2^-8 of
+the exact value's magnitude; on top of that the fp32 rotation and sine / cosine may err by a few
+2^-24 of the operands, taken as 2^-18 (|x_a| + |x_b|) with a wide margin."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import attention as OA
+from oracle import rope as R
+from paper_2504_19867_amd import semipd as S
+from gpu_util import DEV, GpuPool, assert_parity, dev_bf16, f64, host_f64
+
+pytestmark = pytest.mark.gpu
+PRE, DEC = S.SPD_PHASE_PREFILL, S.SPD_PHASE_DECODE
+
+
+def _lib_cfg(o: R.RopeConfig, offset: int = 0):
+    return S.rope_config(theta=o.theta, factor=o.factor, low_freq_factor=o.low_freq_factor, high_freq_factor=o.high_freq_factor,
+                         original_max_pos=o.original_max_pos, rotary_dim=o.rotary_dim, rotary_offset=offset,
+                         interleaved=o.interleaved)
+
+
+def _oracle(x64: np.ndarray, positions, o: R.RopeConfig, offset: int):
+    """The oracle rotates the leading rotary_dim entries: hand it the rotating slice."""
+    out = x64.copy()
+    out[:, :, offset:offset + o.rotary_dim] = R.apply_rope(x64[:, :, offset:offset + o.rotary_dim], positions, o)
+    return out
+
+
+def _pair_magnitude(x64: np.ndarray, o: R.RopeConfig, offset: int):
+    """|x_a| + |x_b| for every entry (0 outside the rotating range)."""
+    mag = np.zeros_like(x64)
+    for a, b in R.pair_index(o):
+        s = np.abs(x64[:, :, offset + a]) + np.abs(x64[:, :, offset + b])
+        mag[:, :, offset + a] = s
+        mag[:, :, offset + b] = s
+    return mag
+
+
+def _assert_rope(got: np.ndarray, want: np.ndarray, mag: np.ndarray, what: str):
+    assert np.isfinite(got).all(), what
+    bar = 2.0 ** -8 * np.abs(want) + 2.0 ** -18 * mag
+    bad = np.abs(got - want) > bar
+    assert not bad.any(), f"{what}: {int(bad.sum())} entries beyond the bar, worst {np.abs(got - want)[bad].max():.3e}"
+
+
+CASES = [
+    # name, oracle config, offset, dim, Hq, Hkv, positions
+    ("llama31 prompt", R.LLAMA31, 0, 128, 32, 8, lambda rng: np.arange(300) + 5),
+    ("llama31 far positions", R.LLAMA31, 0, 128, 8, 2, lambda rng: rng.integers(0, 131072, size=97)),
+    ("plain theta 1e4 dim 64", R.RopeConfig(theta=10000.0, rotary_dim=64), 0, 64, 5, 1, lambda rng: rng.integers(0, 4096, size=33)),
+    ("partial rotary", R.RopeConfig(theta=10000.0, rotary_dim=32), 0, 128, 4, 4, lambda rng: rng.integers(0, 9000, size=50)),
+    ("interleaved tail (MLA rope part)", R.RopeConfig(theta=10000.0, rotary_dim=64, interleaved=True), 128, 192, 16, 16,
+     lambda rng: rng.integers(0, 20000, size=40)),
+    ("decode batch", R.LLAMA31, 0, 128, 32, 8, lambda rng: rng.integers(511, 131072, size=64)),
+    ("one token at position 0", R.LLAMA31, 0, 128, 32, 8, lambda rng: np.array([0])),
+]
+
+
+@pytest.mark.parametrize("name,o,offset,dim,hq,hkv,posf", CASES, ids=[c[0] for c in CASES])
+def test_rope_matches_the_oracle(name, o, offset, dim, hq, hkv, posf):
+    rng = np.random.default_rng(77)
+    pos = np.asarray(posf(rng), dtype=np.int64)
+    T = len(pos)
+    qb, kb = W.normal_bf16(rng, (T, hq, dim)), W.normal_bf16(rng, (T, hkv, dim))
+    ctx = S.Context(0)
+    tq, tk = dev_bf16(qb), dev_bf16(kb)
+    phase = DEC if "decode" in name else PRE
+    ctx.rope_qk(phase, _lib_cfg(o, offset), [int(p) for p in pos], tq, hq, tk, hkv, dim)
+    ctx.phase_sync(phase)
+    for bits, t, what in ((qb, tq, "q"), (kb, tk, "k")):
+        x = f64(bits)
+        _assert_rope(host_f64(t), _oracle(x, pos, o, offset), _pair_magnitude(x, o, offset), f"{name}: {what}")
+    if offset or o.rotary_dim < dim:      # entries outside the rotating range come back bit for bit
+        keep = np.ones(dim, dtype=bool)
+        keep[offset:offset + o.rotary_dim] = False
+        assert np.array_equal(host_f64(tq)[:, :, keep], f64(qb)[:, :, keep])
+
+
+def test_rope_one_tensor_only_and_empty_batch():
+    rng = np.random.default_rng(78)
+    o = R.RopeConfig(theta=500000.0, rotary_dim=128)
+    pos = rng.integers(0, 8192, size=19)
+    xb = W.normal_bf16(rng, (19, 3, 128))
+    ctx = S.Context(0)
+    for which in ("q", "k"):
+        t = dev_bf16(xb)
+        if which == "q":
+            ctx.rope_qk(PRE, _lib_cfg(o), [int(p) for p in pos], t, 3, None, 0, 128)
+        else:
+            ctx.rope_qk(PRE, _lib_cfg(o), [int(p) for p in pos], None, 0, t, 3, 128)
+        ctx.phase_sync(PRE)
+        x = f64(xb)
+        _assert_rope(host_f64(t), _oracle(x, pos, o, 0), _pair_magnitude(x, o, 0), which + " only")
+    t = dev_bf16(xb)
+    ctx.rope_qk(PRE, _lib_cfg(o), [], t, 3, None, 0, 128)             # nothing to do, nothing touched
+    ctx.phase_sync(PRE)
+    assert np.array_equal(host_f64(t), f64(xb))
+
+
+def test_rope_refuses_shapes_the_kernel_cannot_take():
+    ctx = S.Context(0)
+    t = torch.zeros((4, 2, 128), dtype=torch.bfloat16, device=DEV)
+    for cfg, dim in [(S.rope_config(rotary_dim=24), 128),                 # not a multiple of 16
+                     (S.rope_config(rotary_dim=64, rotary_offset=4), 128),  # offset not on a 16-byte piece
+                     (S.rope_config(rotary_dim=128, rotary_offset=8), 128),  # runs past the head
+                     (S.rope_config(rotary_dim=64), 68)]:                   # rows not made of 16-byte pieces
+        with pytest.raises(S.SpdError):
+            ctx.rope_qk(PRE, cfg, [0, 1, 2, 3], t, 2, None, 0, dim)
+    with pytest.raises(S.SpdError):
+        ctx.rope_qk(PRE, S.rope_config(), [0, -1, 2, 3], t, 2, None, 0, 128)   # negative position
+
+
+def test_rope_then_prefill_step_end_to_end():
+    """RoPE on the prefill partition, then the prefill step on the same stream: against the oracle's
+    rotation (rounded to bf16, which is what the interface hands on) followed by its attention."""
+    cfg = W.get_config("c1")
+    L = cfg.layer
+    lens = [37, 150]
+    q, k, v, cu = W.prefill_inputs(L, lens, cfg.seed + 11)
+    pos = np.concatenate([np.arange(n) for n in lens])
+    scale = 1.0 / np.sqrt(L.dim_qk)
+    gp = GpuPool(L, cfg.num_pages)
+    tq, tk, tv = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    out = torch.empty((q.shape[0], L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=DEV)
+    o = R.RopeConfig(theta=500000.0, factor=8.0, rotary_dim=L.dim_qk)
+    gp.ctx.rope_qk(PRE, _lib_cfg(o), [int(p) for p in pos], tq, L.n_q_heads, tk, L.n_kv_heads, L.dim_qk)
+    gp.pool.prefill_step([1, 2], cu, tq, tk, tv, out, L.n_q_heads, L.n_kv_heads, L.dim_qk, L.dim_v, scale)
+    gp.ctx.phase_sync(PRE)
+    q_rot = f64(W.to_bf16_bits(R.apply_rope(f64(q), pos, o)))
+    k_rot = f64(W.to_bf16_bits(R.apply_rope(f64(k), pos, o)))
+    want = OA.prefill_attention(q_rot, k_rot, f64(v), cu, scale)
+    assert_parity(host_f64(out), want, "rope + prefill step")
+    # and the pages hold the rotated keys
+    kg_t = torch.empty((lens[0], L.n_kv_heads, L.dim_qk), dtype=torch.bfloat16, device=DEV)
+    vg_t = torch.empty((lens[0], L.n_kv_heads, L.dim_v), dtype=torch.bfloat16, device=DEV)
+    gp.pool.kv_gather(PRE, 1, lens[0], kg_t, vg_t)
+    gp.ctx.phase_sync(PRE)
+    kg = host_f64(kg_t)
+    _assert_rope(kg, R.apply_rope(f64(k), pos, o)[:lens[0]], _pair_magnitude(f64(k), o, 0)[:lens[0]], "rotated keys in the pages")

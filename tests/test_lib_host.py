@@ -319,3 +319,34 @@ def test_adjuster_argument_checks():
     assert adj.step(0, 50, 50) == (50, 50)      # empty window: unchanged
     assert adj.model() == (0.0, 0.0, 0.0, 0.0, 0.0)
     adj.close()
+
+
+# ----------------------------------------------------------------------------- rotary embedding (host side)
+def test_rope_frequency_table_equals_the_oracle():
+    from oracle import rope as R
+    cases = [
+        (S.rope_config(theta=10000.0, rotary_dim=64), R.RopeConfig(theta=10000.0, rotary_dim=64)),
+        (S.rope_config(factor=8.0), R.LLAMA31),
+        (S.rope_config(theta=1e6, factor=32.0, low_freq_factor=2.0, high_freq_factor=8.0, original_max_pos=4096, rotary_dim=96),
+         R.RopeConfig(theta=1e6, factor=32.0, low_freq_factor=2.0, high_freq_factor=8.0, original_max_pos=4096, rotary_dim=96)),
+    ]
+    for c, o in cases:
+        got, want = np.array(S.rope_inv_freq(c)), R.inv_freq(o)
+        np.testing.assert_allclose(got, want, rtol=1e-15, atol=0)
+
+
+def test_rope_argument_checks():
+    import ctypes as C
+    bad = [
+        S.rope_config(theta=0.0), S.rope_config(factor=0.5), S.rope_config(rotary_dim=0), S.rope_config(rotary_dim=6 + 1),
+        S.rope_config(rotary_offset=-8), S.rope_config(factor=8.0, high_freq_factor=1.0), S.rope_config(factor=8.0, original_max_pos=0),
+    ]
+    buf = (C.c_double * 256)()
+    for c in bad:
+        assert S.lib.spd_rope_inv_freq(C.byref(c), buf, 256) == S.SPD_EINVAL
+    ok = S.rope_config(rotary_dim=64)
+    assert S.lib.spd_rope_inv_freq(C.byref(ok), buf, 31) == S.SPD_EINVAL          # room for fewer than 32
+    assert S.lib.spd_rope_inv_freq(C.byref(ok), None, 64) == S.SPD_EINVAL
+    # the device call: every violated condition is refused before anything is enqueued (a null context too)
+    pos = (C.c_int32 * 4)(0, 1, 2, 3)
+    assert S.lib.spd_rope_qk(None, 0, C.byref(ok), pos, 4, 16, 2, None, 0, 64) == S.SPD_EINVAL
