@@ -81,7 +81,11 @@ extern "C" int spd_rope_qk(spd_ctx* ctx, int phase, const spd_rope_config* cfg, 
   // the kernel reads the table and the positions straight out of the pinned buffer
   const void* qq = q ? q : k;
   const int hq = q ? n_q_heads : n_kv_heads;
+  st_rc = kernel_timing_mark(ctx, phase, 0, stream);
+  if (st_rc != SPD_OK) return st_rc;
   SPD_HIP(launch_rope((void*)qq, hq, q ? k : nullptr, n_kv_heads, dim, cfg->rotary_dim, cfg->rotary_offset, cfg->interleaved != 0,
                       n_tokens, (const int32_t*)((const char*)host_dev + w_bytes), (const double*)host_dev, stream));
+  st_rc = kernel_timing_mark(ctx, phase, 1, stream);
+  if (st_rc != SPD_OK) return st_rc;
   return stage_commit(ctx, phase, st, w_bytes + p_bytes, stream, false);
 }
