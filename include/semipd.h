@@ -178,7 +178,14 @@ int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_batch* batc
  *        v_new NULL, out device [B, n_q_heads, 512];
  *        s[h,t] = scale * q[b,h,:] . c_t,  out[b,h,:] = sum_t softmax_t(s[h,:]) * c_t[0:512].
  * n_q_heads must be a multiple of n_kv_heads with at most 16 query heads per KV head; scale
- * must be positive and finite. */
+ * must be positive and finite.
+ * With `rope` non-NULL (declared further down; paper, Evaluation "Implementation based on
+ * DistServe": the RoPE kernel) q and k_new are the vectors BEFORE the rotary embedding: the step
+ * rotates request b's query and new key by position ctx_lens[b] - 1, the query into a library
+ * workspace (the caller's q, k_new are left as they are), the key straight into the page, in the one
+ * launch that appends; the attention then reads the rotated query.  The rotating range must fit the
+ * head (rotary_offset + rotary_dim <= dim_k; multiples of 8 and 16) or the call is SPD_EINVAL. */
+struct spd_rope_config;
 typedef struct {
   int32_t n_req;
   const uint64_t* req_ids; /* host [n_req] */
@@ -189,6 +196,7 @@ typedef struct {
   void* out;
   int32_t n_q_heads;
   float scale;
+  const struct spd_rope_config* rope; /* NULL, or: q and k_new are given before RoPE (see below) */
 } spd_decode_batch;
 int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* batch);
 
@@ -207,7 +215,7 @@ int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* batch)
  *     otherwise: s = (original_max_pos / L - low_freq_factor) / (high_freq_factor - low_freq_factor),
  *                w_i' = (1 - s) w_i / factor + s w_i.
  * Angles are formed in fp64, the rotation in fp32, the result rounded to bf16 (nearest even). */
-typedef struct {
+typedef struct spd_rope_config {
   double theta;             /* > 0, e.g. 500000 (Llama-3) */
   double factor;            /* >= 1; 1 = no frequency scaling (the three fields below are then unused) */
   double low_freq_factor;   /* > 0 */

@@ -145,6 +145,9 @@ int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream
 int stage_host_as_device(spd_stage* st, void** out);   // device-readable address of the pinned host buffer
 int workspace_reserve(spd_ctx* ctx, int phase, size_t bytes, char** out);
 int kernel_timing_mark(spd_ctx* ctx, int phase, int which, hipStream_t stream);   // which: 0 begin, 1 end
+// rope.cpp: SPD_OK if the configuration is well-formed; the frequency table (rotary_dim / 2 doubles)
+int rope_config_check(const spd_rope_config* c);
+void rope_frequencies(const spd_rope_config* c, double* out);
 
 // kernel launchers (kernels_*.hip); all enqueue on `stream` and return the launch status
 // d_tiles may be device-readable pinned host memory.  With copy_dst non-null the same launch also
@@ -168,6 +171,10 @@ hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out
 // d_pos, d_w may be device-readable pinned host memory
 hipError_t launch_rope(void* q, int n_q_heads, void* k, int n_kv_heads, int dim, int rot, int off, bool interleaved,
                        int n_tokens, const int32_t* d_pos, const double* d_w, hipStream_t stream);
+// decode step with RoPE: rotated query copy + rotated key (and value) appended to the page, one launch
+hipError_t launch_rope_append(const PoolGeom& g, char* pool_base, const TileDesc* d_descs, const int32_t* d_ctx_lens, int B,
+                              const void* q, void* q_out, int Hq, int dq, const void* k_new, const void* v_new, int rot,
+                              int off, bool interleaved, const double* d_w, hipStream_t stream);
 hipError_t launch_probe(int32_t* d_ids, int n_blocks, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, int cus, hipStream_t stream);
 bool prefill_shape_supported(int dqk, int dv);

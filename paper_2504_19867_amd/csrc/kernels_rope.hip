@@ -115,3 +115,114 @@ hipError_t launch_rope(void* q, int n_q_heads, void* k, int n_kv_heads, int dim,
 }
 
 }  // namespace spd
+
+// ------------------------------------------------------------------------------------------------
+// Decode step with RoPE: one launch rotates the new token's query (into a workspace copy, the caller's
+// tensor is left alone) and key, and appends the rotated key and the value to the request's page
+// (paper, Evaluation "Implementation based on DistServe": the RoPE kernel; Background: the decode
+// phase appends the new key / value to the cache).  One workgroup per request; the token's position
+// is ctx_len - 1.  Sixteen-byte pieces of 8 entries: a piece inside the rotating range reads its
+// partner piece as well and produces its own 8 rotated entries.
+namespace spd {
+
+struct RopeAppendArgs {
+  const unsigned short* q;
+  unsigned short* q_out;
+  const unsigned short* k;
+  const unsigned short* v;
+  int Hq, Hkv, dq, dk, dv;
+  int rot, off, interleaved;
+  const double* w;
+  const int32_t* ctx_lens;
+  const TileDesc* descs;
+  char* base;
+  uint64_t page_bytes;
+  uint32_t head_bytes, tile_bytes, tile_k_bytes;
+  int natural;
+};
+
+// the 8 entries starting at entry e0 of a head vector `row`, rotated
+__device__ inline uint4 rope_piece(const unsigned short* row, int e0, int off, int rot, bool interleaved, const float* cs,
+                                   const float* sn) {
+  const uint4 own = *(const uint4*)(row + e0);
+  if (e0 < off || e0 >= off + rot) return own;
+  uint32_t ow[4] = {own.x, own.y, own.z, own.w};
+  if (interleaved) {
+    const int p0 = (e0 - off) >> 1;               // first pair of the piece
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float xa = bf_lo(ow[j]), xb = bf_hi(ow[j]);
+      ow[j] = pack_bf16(xa * cs[p0 + j] - xb * sn[p0 + j], xb * cs[p0 + j] + xa * sn[p0 + j]);
+    }
+  } else {
+    const int half = rot >> 1;
+    const bool first = e0 < off + half;           // this piece holds the a side of its 8 pairs
+    const int p0 = first ? e0 - off : e0 - off - half;
+    const uint4 oth = *(const uint4*)(row + (first ? e0 + half : e0 - half));
+    const uint32_t tw[4] = {oth.x, oth.y, oth.z, oth.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float m0 = bf_lo(ow[j]), m1 = bf_hi(ow[j]), o0 = bf_lo(tw[j]), o1 = bf_hi(tw[j]);
+      const float c0 = cs[p0 + 2 * j], s0 = sn[p0 + 2 * j], c1 = cs[p0 + 2 * j + 1], s1 = sn[p0 + 2 * j + 1];
+      // a side: x_a cos - x_b sin;  b side: x_b cos + x_a sin
+      ow[j] = first ? pack_bf16(m0 * c0 - o0 * s0, m1 * c1 - o1 * s1) : pack_bf16(m0 * c0 + o0 * s0, m1 * c1 + o1 * s1);
+    }
+  }
+  return uint4{ow[0], ow[1], ow[2], ow[3]};
+}
+
+__global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs a) {
+  __shared__ float cs[128], sn[128];              // rotary_dim <= 256
+  const int r = blockIdx.x;
+  const int npairs = a.rot >> 1;
+  const double p = (double)(a.ctx_lens[r] - 1);
+  for (int i = threadIdx.x; i < npairs; i += blockDim.x) {
+    const double turns = p * a.w[i] * 0.15915494309189535;
+    const float ang = (float)((turns - __builtin_rint(turns)) * 6.283185307179586);
+    sincosf(ang, &sn[i], &cs[i]);
+  }
+  __syncthreads();
+  // query: rotated copy
+  const int qp = a.dq >> 3;
+  for (int i = threadIdx.x; i < a.Hq * qp; i += blockDim.x) {
+    const int h = i / qp, c = i % qp;
+    const unsigned short* row = a.q + ((size_t)r * a.Hq + h) * a.dq;
+    *(uint4*)(a.q_out + ((size_t)r * a.Hq + h) * a.dq + 8 * c) = rope_piece(row, 8 * c, a.off, a.rot, a.interleaved != 0, cs, sn);
+  }
+  if (a.k == nullptr) return;
+  // key: rotated, straight into the page; value: as it is
+  const TileDesc d = a.descs[r];
+  const int t = d.t_begin;
+  const int kp = a.dk >> 3;
+  for (int i = threadIdx.x; i < a.Hkv * kp; i += blockDim.x) {
+    const int g = i / kp, c = i % kp;
+    const unsigned short* row = a.k + ((size_t)r * a.Hkv + g) * a.dk;
+    char* tile = a.base + (uint64_t)d.page * a.page_bytes + (uint64_t)g * a.head_bytes + (uint64_t)d.sub * a.tile_bytes;
+    const size_t off = a.natural ? (size_t)t * a.dk * 2 + (size_t)c * 16 : ((size_t)(c * 16 + t) << 4);
+    *(uint4*)(tile + off) = rope_piece(row, 8 * c, a.off, a.rot, a.interleaved != 0, cs, sn);
+  }
+  if (a.v == nullptr) return;
+  for (int i = threadIdx.x; i < a.Hkv * a.dv; i += blockDim.x) {
+    const int g = i / a.dv, dd = i % a.dv;
+    char* tile = a.base + (uint64_t)d.page * a.page_bytes + (uint64_t)g * a.head_bytes + (uint64_t)d.sub * a.tile_bytes;
+    ((unsigned short*)(tile + a.tile_k_bytes))[v_elem_offset(t, dd)] = a.v[((size_t)r * a.Hkv + g) * a.dv + dd];
+  }
+}
+
+hipError_t launch_rope_append(const PoolGeom& g, char* pool_base, const TileDesc* d_descs, const int32_t* d_ctx_lens, int B,
+                              const void* q, void* q_out, int Hq, int dq, const void* k_new, const void* v_new, int rot,
+                              int off, bool interleaved, const double* d_w, hipStream_t stream) {
+  if (B <= 0) return hipSuccess;
+  RopeAppendArgs a;
+  a.q = (const unsigned short*)q; a.q_out = (unsigned short*)q_out;
+  a.k = (const unsigned short*)k_new; a.v = (const unsigned short*)v_new;
+  a.Hq = Hq; a.Hkv = g.Hkv; a.dq = dq; a.dk = g.dk; a.dv = g.dv;
+  a.rot = rot; a.off = off; a.interleaved = interleaved ? 1 : 0;
+  a.w = d_w; a.ctx_lens = d_ctx_lens; a.descs = d_descs;
+  a.base = pool_base; a.page_bytes = g.page_bytes; a.head_bytes = g.head_bytes; a.tile_bytes = g.tile_bytes;
+  a.tile_k_bytes = g.tile_k_bytes; a.natural = g.kind == SPD_KV_MLA_LATENT ? 1 : 0;
+  hipLaunchKernelGGL(rope_append_kernel, dim3((unsigned)B), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace spd

@@ -12,7 +12,8 @@
 
 using namespace spd;
 
-static int rope_check(const spd_rope_config* c) {
+namespace spd {
+int rope_config_check(const spd_rope_config* c) {
   if (!c) return SPD_EINVAL;
   if (!(c->theta > 0.0) || !std::isfinite(c->theta) || !(c->factor >= 1.0) || !std::isfinite(c->factor)) return SPD_EINVAL;
   if (c->rotary_dim <= 0 || c->rotary_dim % 2 || c->rotary_offset < 0) return SPD_EINVAL;
@@ -22,7 +23,7 @@ static int rope_check(const spd_rope_config* c) {
   return SPD_OK;
 }
 
-static void rope_frequencies(const spd_rope_config* c, double* out) {
+void rope_frequencies(const spd_rope_config* c, double* out) {
   const double two_pi = 6.283185307179586476925286766559;
   for (int i = 0; i < c->rotary_dim / 2; ++i) {
     double w = std::pow(c->theta, -2.0 * i / c->rotary_dim);
@@ -40,9 +41,10 @@ static void rope_frequencies(const spd_rope_config* c, double* out) {
     out[i] = w;
   }
 }
+}  // namespace spd
 
 extern "C" int spd_rope_inv_freq(const spd_rope_config* cfg, double* out, int32_t cap) {
-  const int rc = rope_check(cfg);
+  const int rc = rope_config_check(cfg);
   if (rc != SPD_OK) return rc;
   if (!out || cap < cfg->rotary_dim / 2) return SPD_EINVAL;
   rope_frequencies(cfg, out);
@@ -52,7 +54,7 @@ extern "C" int spd_rope_inv_freq(const spd_rope_config* cfg, double* out, int32_
 extern "C" int spd_rope_qk(spd_ctx* ctx, int phase, const spd_rope_config* cfg, const int32_t* positions, int32_t n_tokens,
                            void* q, int32_t n_q_heads, void* k, int32_t n_kv_heads, int32_t dim) {
   if (!ctx || (phase != SPD_PHASE_PREFILL && phase != SPD_PHASE_DECODE)) return SPD_EINVAL;
-  const int rc = rope_check(cfg);
+  const int rc = rope_config_check(cfg);
   if (rc != SPD_OK) return rc;
   if (n_tokens < 0 || (n_tokens > 0 && !positions)) return SPD_EINVAL;
   if (!q && !k) return SPD_EINVAL;

@@ -273,6 +273,13 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
       for (int r2 = 0; r2 < r; ++r2)
         if (b->req_ids[r2] == b->req_ids[r]) return SPD_EINVAL;
   }
+  if (b->rope) {
+    int rrc = rope_config_check(b->rope);
+    if (rrc != SPD_OK) return rrc;
+    if (b->rope->rotary_dim % 16 || b->rope->rotary_dim > 256 || b->rope->rotary_offset % 8 ||
+        b->rope->rotary_offset + b->rope->rotary_dim > g.dk)
+      return SPD_EINVAL;
+  }
   if (ctx->device < 0) return SPD_ESTATE;
 
   const int B = b->n_req;
@@ -309,14 +316,19 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
   size_t off_bt = align16(sizeof(int32_t) * (size_t)B);
   size_t off_items = align16(off_bt + sizeof(int32_t) * (size_t)B * bt_stride);
   size_t off_desc = align16(off_items + sizeof(int32_t) * 2 * (size_t)n_items);
-  size_t bytes = off_desc + (append ? sizeof(TileDesc) * (size_t)B : 0);
+  size_t off_w = align16(off_desc + (append ? sizeof(TileDesc) * (size_t)B : 0));
+  size_t bytes = off_w + (b->rope ? sizeof(double) * (size_t)(b->rope->rotary_dim / 2) : 0);
   spd_stage* st;
   if ((rc = stage_acquire(ctx, SPD_PHASE_DECODE, bytes, &st)) != SPD_OK) return rc;
   char* ws = nullptr;
-  size_t ws_o_bytes = max_chunks > 1 ? sizeof(float) * (size_t)B * b->n_q_heads * max_chunks * g.dv : 0;
-  size_t ws_ml_bytes = max_chunks > 1 ? sizeof(float) * (size_t)B * b->n_q_heads * max_chunks * 2 : 0;
-  if (max_chunks > 1 && (rc = workspace_reserve(ctx, SPD_PHASE_DECODE, ws_o_bytes + ws_ml_bytes, &ws)) != SPD_OK)
+  size_t ws_o_bytes = max_chunks > 1 ? align16(sizeof(float) * (size_t)B * b->n_q_heads * max_chunks * g.dv) : 0;
+  size_t ws_ml_bytes = max_chunks > 1 ? align16(sizeof(float) * (size_t)B * b->n_q_heads * max_chunks * 2) : 0;
+  size_t ws_q_bytes = b->rope ? (size_t)B * b->n_q_heads * g.dk * 2 : 0;      // the rotated query
+  if (ws_o_bytes + ws_ml_bytes + ws_q_bytes > 0 &&
+      (rc = workspace_reserve(ctx, SPD_PHASE_DECODE, ws_o_bytes + ws_ml_bytes + ws_q_bytes, &ws)) != SPD_OK)
     return rc;
+  char* ws_q = b->rope ? ws + ws_o_bytes + ws_ml_bytes : nullptr;
+  if (b->rope) rope_frequencies(b->rope, (double*)(st->host + off_w));
 
   int32_t* h_ctx = (int32_t*)st->host;
   int32_t* h_bt = (int32_t*)(st->host + off_bt);
@@ -355,17 +367,25 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
   }
   if (ctx->kernel_timing) SPD_HIP(hipEventRecord(ds.ev_start, stream));
   if ((rc = stage_commit(ctx, SPD_PHASE_DECODE, st, bytes, stream)) != SPD_OK) return rc;
-  if (append)
+  const void* att_q = b->q;
+  if (b->rope) {
+    SPD_HIP(launch_rope_append(g, pool->base, (const TileDesc*)(st->dev + off_desc), (const int32_t*)st->dev, B, b->q, ws_q,
+                               b->n_q_heads, g.dk, append ? b->k_new : nullptr, append ? b->v_new : nullptr,
+                               b->rope->rotary_dim, b->rope->rotary_offset, b->rope->interleaved != 0,
+                               (const double*)(st->dev + off_w), stream));
+    att_q = ws_q;
+  } else if (append) {
     SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(st->dev + off_desc), B, b->k_new, b->v_new, stream));
+  }
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 0, stream)) != SPD_OK) return rc;
   if (mla)
-    SPD_HIP(launch_decode_mla(g, pool->base, b->q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
+    SPD_HIP(launch_decode_mla(g, pool->base, att_q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
                               bt_stride, st->dev + off_items, n_items, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks,
-                              (float*)ws, (float*)(ws ? ws + ws_o_bytes : nullptr), stream));
+                              (float*)(max_chunks > 1 ? ws : nullptr), (float*)(max_chunks > 1 ? ws + ws_o_bytes : nullptr), stream));
   else
-    SPD_HIP(launch_decode_gqa(g, pool->base, b->q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
+    SPD_HIP(launch_decode_gqa(g, pool->base, att_q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
                               bt_stride, st->dev + off_items, n_items, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks,
-                              (float*)ws, (float*)(ws ? ws + ws_o_bytes : nullptr), stream));
+                              (float*)(max_chunks > 1 ? ws : nullptr), (float*)(max_chunks > 1 ? ws + ws_o_bytes : nullptr), stream));
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 1, stream)) != SPD_OK) return rc;
   if (ctx->kernel_timing) {
     SPD_HIP(hipEventRecord(ds.ev_end, stream));

@@ -71,7 +71,7 @@ class spd_prefill_batch(C.Structure):
 class spd_decode_batch(C.Structure):
     _fields_ = [("n_req", C.c_int32), ("req_ids", C.POINTER(C.c_uint64)), ("ctx_lens", C.POINTER(C.c_int32)),
                 ("q", C.c_void_p), ("k_new", C.c_void_p), ("v_new", C.c_void_p), ("out", C.c_void_p),
-                ("n_q_heads", C.c_int32), ("scale", C.c_float)]
+                ("n_q_heads", C.c_int32), ("scale", C.c_float), ("rope", C.POINTER(spd_rope_config))]
 
 
 def _load() -> C.CDLL:
@@ -383,13 +383,14 @@ class Pool:
         _check(lib.spd_prefill_step(self.ctx.h, self.h, C.byref(batch)), "spd_prefill_step")
 
     def make_decode_batch(self, req_ids: Sequence[int], ctx_lens: Sequence[int], q, out, n_q_heads: int,
-                          scale: float, k_new=None, v_new=None):
+                          scale: float, k_new=None, v_new=None, rope: Optional[spd_rope_config] = None):
         """Marshal once; the returned object can be passed to decode_step_batch repeatedly."""
         n = len(req_ids)
         ids = (C.c_uint64 * n)(*req_ids)
         lens = (C.c_int32 * n)(*[int(x) for x in ctx_lens])
-        b = spd_decode_batch(n, ids, lens, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), n_q_heads, scale)
-        b._keep = (ids, lens, q, out, k_new, v_new)
+        rp = C.pointer(rope) if rope is not None else None
+        b = spd_decode_batch(n, ids, lens, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), n_q_heads, scale, rp)
+        b._keep = (ids, lens, q, out, k_new, v_new, rope, rp)
         return b
 
     def decode_worker_start(self, batches):
@@ -410,5 +411,5 @@ class Pool:
     def decode_step_batch(self, batch) -> None:
         _check(lib.spd_decode_step(self.ctx.h, self.h, C.byref(batch)), "spd_decode_step")
 
-    def decode_step(self, req_ids, ctx_lens, q, out, n_q_heads: int, scale: float, k_new=None, v_new=None) -> None:
-        self.decode_step_batch(self.make_decode_batch(req_ids, ctx_lens, q, out, n_q_heads, scale, k_new, v_new))
+    def decode_step(self, req_ids, ctx_lens, q, out, n_q_heads: int, scale: float, k_new=None, v_new=None, rope=None) -> None:
+        self.decode_step_batch(self.make_decode_batch(req_ids, ctx_lens, q, out, n_q_heads, scale, k_new, v_new, rope))

@@ -142,3 +142,97 @@ def test_rope_then_prefill_step_end_to_end():
     gp.ctx.phase_sync(PRE)
     kg = host_f64(kg_t)
     _assert_rope(kg, R.apply_rope(f64(k), pos, o)[:lens[0]], _pair_magnitude(f64(k), o, 0)[:lens[0]], "rotated keys in the pages")
+
+
+# ----------------------------------------------------------------------------- fused into the decode step
+def _round_bf16(x64: np.ndarray) -> np.ndarray:
+    return f64(W.to_bf16_bits(x64))
+
+
+def test_decode_step_with_rope_rotates_query_and_appended_key_gqa():
+    """rope in the decode batch: query and new key are rotated by position ctx_len - 1, the key goes to the
+    page rotated, the caller's tensors stay as they were; several appends across a page border."""
+    import math
+    from test_gpu_parity import fill_decode_contexts, oracle_decode
+    layer = W.LayerShape("gqa", 8, 2, 128, 128, 16)
+    gp = GpuPool(layer, 32, poison=True)
+    o = R.RopeConfig(theta=500000.0, factor=8.0, rotary_dim=128)
+    cfg = _lib_cfg(o)
+    scale = 1.0 / math.sqrt(128)
+    start = (14, 31)
+    _, ks, vs, ids = fill_decode_contexts(gp, start, seed=141)           # cached keys: taken as already rotated
+    ks, vs = [x.copy() for x in ks], [x.copy() for x in vs]
+    rng = np.random.default_rng(142)
+    lens = list(start)
+    for step in range(4):
+        lens = [n + 1 for n in lens]
+        knew, vnew, qn = (W.normal_bf16(rng, (2, 2, 128)), W.normal_bf16(rng, (2, 2, 128)), W.normal_bf16(rng, (2, 8, 128)))
+        tq, tk = dev_bf16(qn), dev_bf16(knew)
+        out = torch.empty((2, 8, 128), dtype=torch.bfloat16, device=DEV)
+        gp.pool.decode_step(ids, lens, tq, out, 8, scale, k_new=tk, v_new=dev_bf16(vnew), rope=cfg)
+        gp.ctx.phase_sync(DEC)
+        assert np.array_equal(host_f64(tq), f64(qn)) and np.array_equal(host_f64(tk), f64(knew))    # inputs untouched
+        pos = [n - 1 for n in lens]
+        q_rot = _round_bf16(R.apply_rope(f64(qn), pos, o))
+        k_rot = W.to_bf16_bits(R.apply_rope(f64(knew), pos, o))
+        for i in range(2):
+            ks[i] = np.concatenate([ks[i], k_rot[i][None]])
+            vs[i] = np.concatenate([vs[i], vnew[i][None]])
+        want = np.stack([OA.decode_attention(q_rot[i], f64(ks[i]), f64(vs[i]), scale) for i in range(2)])
+        assert_parity(host_f64(out), want, f"rope + append step {step}")
+        # the page holds the rotated key, to the rotation's own bar
+        for i in range(2):
+            kg = torch.empty((lens[i], 2, 128), dtype=torch.bfloat16, device=DEV)
+            vg = torch.empty((lens[i], 2, 128), dtype=torch.bfloat16, device=DEV)
+            gp.pool.kv_gather(DEC, ids[i], lens[i], kg, vg)
+            gp.ctx.phase_sync(DEC)
+            x = f64(knew)[i:i + 1]
+            _assert_rope(host_f64(kg)[-1:], R.apply_rope(x, [pos[i]], o), _pair_magnitude(x, o, 0), "appended key")
+            assert np.array_equal(host_f64(vg)[-1], f64(vnew)[i])
+    # attend-only with rope: the query alone is rotated
+    qn = W.normal_bf16(rng, (2, 8, 128))
+    out = torch.empty((2, 8, 128), dtype=torch.bfloat16, device=DEV)
+    gp.pool.decode_step(ids, lens, dev_bf16(qn), out, 8, scale, rope=cfg)
+    gp.ctx.phase_sync(DEC)
+    q_rot = _round_bf16(R.apply_rope(f64(qn), [n - 1 for n in lens], o))
+    want = np.stack([OA.decode_attention(q_rot[i], f64(ks[i]), f64(vs[i]), scale) for i in range(2)])
+    assert_parity(host_f64(out), want, "rope, attend only")
+    # a rotating range that does not fit the head is refused, nothing changes
+    before = gp.pool.stats()
+    with pytest.raises(S.SpdError):
+        gp.pool.decode_step(ids, [n + 1 for n in lens], dev_bf16(qn), out, 8, scale, k_new=dev_bf16(knew), v_new=dev_bf16(vnew),
+                            rope=S.rope_config(rotary_dim=128, rotary_offset=64))
+    assert gp.pool.stats() == before
+    gp.close()
+
+
+def test_decode_step_with_rope_on_the_latent_tail_mla():
+    """MLA: the last 64 of the 576 latent entries are the decoupled RoPE part (interleaved pairs); the
+    absorbed query carries its RoPE part in the same place."""
+    import math
+    from test_gpu_mla import fill_latent, mla_layer
+    layer = mla_layer(16)
+    gp = GpuPool(layer, 16, poison=True)
+    o = R.RopeConfig(theta=10000.0, rotary_dim=64, interleaved=True)
+    cfg = _lib_cfg(o, offset=512)
+    scale = 1.0 / math.sqrt(192)
+    start = (62, 127)
+    _, cs, ids = fill_latent(gp, start, seed=151)
+    cs = [c.copy() for c in cs]
+    rng = np.random.default_rng(152)
+    lens = list(start)
+    for step in range(3):
+        lens = [n + 1 for n in lens]
+        cnew = W.normal_bf16(rng, (2, 576))
+        qn = W.normal_bf16(rng, (2, 16, 576), 0.3)
+        out = torch.empty((2, 16, 512), dtype=torch.bfloat16, device=DEV)
+        gp.pool.decode_step(ids, lens, dev_bf16(qn), out, 16, scale, k_new=dev_bf16(cnew), rope=cfg)
+        gp.ctx.phase_sync(DEC)
+        pos = [n - 1 for n in lens]
+        q_rot = _round_bf16(_oracle(f64(qn), pos, o, 512))
+        c_rot = W.to_bf16_bits(_oracle(f64(cnew)[:, None, :], pos, o, 512)[:, 0, :])
+        for i in range(2):
+            cs[i] = np.concatenate([cs[i], c_rot[i][None]])
+        want = np.stack([OA.mla_decode_latent(q_rot[i], f64(cs[i]), scale, 512) for i in range(2)])
+        assert_parity(host_f64(out), want, f"mla rope + append step {step}")
+    gp.close()
