@@ -87,7 +87,8 @@ __global__ __launch_bounds__(256) void kv_write_kernel(char* __restrict__ base, 
   }
 }
 
-// Inverse of kv_write_kernel, element by element through the layout functions.
+// Inverse of kv_write_kernel, with the same 16-byte pieces: K pieces go straight back to their rows,
+// the V tile is un-transposed through LDS and leaves as 16-byte row pieces.
 __global__ __launch_bounds__(256) void kv_gather_kernel(const char* __restrict__ base, uint64_t page_bytes,
                                                         uint32_t head_bytes, uint32_t tile_bytes,
                                                         uint32_t tile_k_bytes, const TileDesc* __restrict__ descs,
@@ -96,17 +97,34 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(const char* __restrict__
   const TileDesc d = descs[blockIdx.x];
   const int g = blockIdx.y;
   const char* tile = base + (uint64_t)d.page * page_bytes + (uint64_t)g * head_bytes + (uint64_t)d.sub * tile_bytes;
-  const bf16_t* kt = (const bf16_t*)tile;
-  const bf16_t* vt = (const bf16_t*)(tile + tile_k_bytes);
-  const int nt = d.t_end - d.t_begin;
-  for (int i = threadIdx.x; i < nt * dk; i += blockDim.x) {
-    const int t = d.t_begin + i / dk, dd = i % dk;
-    k_out[((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dk + dd] = kt[natural ? (uint32_t)(t * dk + dd) : k_elem_offset(t, dd)];
+  const int k_items = (dk >> 3) * TILE_T;
+  for (int i = threadIdx.x; i < k_items; i += blockDim.x) {
+    const int t = i & 15, c = i >> 4;
+    if (t >= d.t_begin && t < d.t_end) {
+      const size_t off = natural ? (size_t)t * dk * 2 + (size_t)c * 16 : ((size_t)(c * 16 + t) << 4);
+      *(uint4*)(k_out + ((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dk + c * 8) = *(const uint4*)(tile + off);
+    }
   }
   if (v_out == nullptr) return;
-  for (int i = threadIdx.x; i < nt * dv; i += blockDim.x) {
-    const int t = d.t_begin + i / dv, dd = i % dv;
-    v_out[((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dv + dd] = vt[v_elem_offset(t, dd)];
+  __shared__ bf16_t vs[TILE_T][256 + 8];            // dv <= 256; 8 elements of padding per row
+  const bf16_t* vt = (const bf16_t*)(tile + tile_k_bytes);
+  const int v_items = (dv >> 5) * 64;               // 16-byte pieces of the tile: (d/32, token quad, d%16)
+  for (int i = threadIdx.x; i < v_items; i += blockDim.x) {
+    const int m = i & 15, c4 = (i >> 4) & 3, blk2 = i >> 6;
+    const uint4 pk = *(const uint4*)(vt + ((size_t)((blk2 * 4 + c4) * 16 + m) << 3));
+    const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {                   // element e = (d/16)%2 * 4 + token%4
+      const int par = e >> 2, tt = e & 3;
+      vs[4 * c4 + tt][32 * blk2 + 16 * par + m] = (bf16_t)(w[e >> 1] >> (16 * (e & 1)));
+    }
+  }
+  __syncthreads();
+  const int pieces = (dv >> 3) * TILE_T;
+  for (int i = threadIdx.x; i < pieces; i += blockDim.x) {
+    const int t = i / (dv >> 3), c = i % (dv >> 3);
+    if (t >= d.t_begin && t < d.t_end)
+      *(uint4*)(v_out + ((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dv + c * 8) = *(const uint4*)&vs[t][c * 8];
   }
 }
 
