@@ -33,28 +33,43 @@ __global__ __launch_bounds__(256) void kv_write_kernel(char* __restrict__ base, 
   const int g = blockIdx.y;
   char* tile = base + (uint64_t)d.page * page_bytes + (uint64_t)g * head_bytes + (uint64_t)d.sub * tile_bytes;
   // K part: [chunk][token][8 dims] (GQA) or natural [token][dim] rows (MLA latent), one 16-byte
-  // piece per (chunk, token)
+  // piece per (chunk, token).  For the GQA order the pieces cross LDS so that both the row reads
+  // (consecutive chunks of a token) and the page writes (consecutive tokens of a chunk) are contiguous.
   const int k_items = (dk >> 3) * TILE_T;
-  for (int i = threadIdx.x; i < k_items; i += blockDim.x) {
-    const int t = i & 15, c = i >> 4;
-    if (t >= d.t_begin && t < d.t_end) {
-      const bf16_t* src = k + ((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dk + c * 8;
-      const size_t off = natural ? (size_t)t * dk * 2 + (size_t)c * 16 : ((size_t)(c * 16 + t) << 4);
-      *(uint4*)(tile + off) = *(const uint4*)src;
+  if (natural) {
+    for (int i = threadIdx.x; i < k_items; i += blockDim.x) {
+      const int t = i / (dk >> 3), c = i % (dk >> 3);
+      if (t >= d.t_begin && t < d.t_end)
+        *(uint4*)(tile + (size_t)t * dk * 2 + (size_t)c * 16) =
+            *(const uint4*)(k + ((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dk + c * 8);
+    }
+  }
+  // V part: [d/32][token quad][d%16][(d/16)%2][4 tokens], one 16-byte piece per (d/32, quad, d%16).
+  // The tile's rows go through LDS (16-byte loads of 8 dims, [token][dim]) and come out transposed.
+  __shared__ uint4 ks[TILE_T][32 + 1];              // dk <= 256: 32 pieces per token, one of padding
+  __shared__ bf16_t vs[TILE_T][256 + 8];            // dv <= 256; 8 elements of padding per row
+  bf16_t* vt = (bf16_t*)(tile + tile_k_bytes);
+  const int pieces = v ? (dv >> 3) * TILE_T : 0;
+  // all row reads of the workgroup (K and V) are issued before anything waits for them
+  for (int i = threadIdx.x; i < max(natural ? 0 : k_items, pieces); i += blockDim.x) {
+    uint4 kr = uint4{0, 0, 0, 0}, vr = uint4{0, 0, 0, 0};
+    const int tk = i / (dk >> 3), ck = i % (dk >> 3);
+    const bool k_ok = !natural && i < k_items && tk >= d.t_begin && tk < d.t_end;
+    if (k_ok) kr = *(const uint4*)(k + ((size_t)(d.src_row + tk - d.t_begin) * Hkv + g) * dk + ck * 8);
+    const int tv = i / max(dv >> 3, 1), cv = i % max(dv >> 3, 1);
+    const bool v_ok = i < pieces && tv >= d.t_begin && tv < d.t_end;
+    if (v_ok) vr = *(const uint4*)(v + ((size_t)(d.src_row + tv - d.t_begin) * Hkv + g) * dv + cv * 8);
+    if (k_ok) ks[tk][ck] = kr;
+    if (v_ok) *(uint4*)&vs[tv][cv * 8] = vr;
+  }
+  __syncthreads();
+  if (!natural) {
+    for (int i = threadIdx.x; i < k_items; i += blockDim.x) {
+      const int t = i & 15, c = i >> 4;
+      if (t >= d.t_begin && t < d.t_end) *(uint4*)(tile + ((size_t)(c * 16 + t) << 4)) = ks[t][c];
     }
   }
   if (v == nullptr) return;
-  // V part: [d/32][token quad][d%16][(d/16)%2][4 tokens], one 16-byte piece per (d/32, quad, d%16).
-  // The tile's rows go through LDS (16-byte loads of 8 dims, [token][dim]) and come out transposed.
-  __shared__ bf16_t vs[TILE_T][256 + 8];            // dv <= 256; 8 elements of padding per row
-  bf16_t* vt = (bf16_t*)(tile + tile_k_bytes);
-  const int pieces = (dv >> 3) * TILE_T;
-  for (int i = threadIdx.x; i < pieces; i += blockDim.x) {
-    const int t = i / (dv >> 3), c = i % (dv >> 3);
-    if (t >= d.t_begin && t < d.t_end)
-      *(uint4*)&vs[t][c * 8] = *(const uint4*)(v + ((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dv + c * 8);
-  }
-  __syncthreads();
   const int v_items = (dv >> 5) * 64;
   for (int i = threadIdx.x; i < v_items; i += blockDim.x) {
     const int m = i & 15, c4 = (i >> 4) & 3, blk2 = i >> 6;
