@@ -187,7 +187,6 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   if ((rc = stage_host_as_device(st, &host_dev)) != SPD_OK) return rc;
   SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)((const char*)host_dev + off_desc), (int)descs.size(), page_src_k,
                           page_src_v, stream, st->dev, host_dev, bytes));
-  if ((rc = stage_commit(ctx, SPD_PHASE_PREFILL, st, bytes, stream, false)) != SPD_OK) return rc;
   const void *att_k = b->k, *att_v = b->v;
   if (chunked) {
     // every request's rows 0 .. prefix+len-1, the new ones included, back out of the pages
@@ -200,6 +199,9 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   SPD_HIP(launch_prefill(b->q, att_k, att_v, b->out, (const PrefillWork*)st->dev, (int)work.size(), b->n_q_heads,
                          b->n_kv_heads, b->dim_qk, b->dim_v, b->scale, stream));
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_PREFILL, 1, stream)) != SPD_OK) return rc;
+  // the staging buffer is free again once the kernels above have run; its event goes behind the
+  // attention kernel so that nothing sits between the page write and the attention launch
+  if ((rc = stage_commit(ctx, SPD_PHASE_PREFILL, st, bytes, stream, false)) != SPD_OK) return rc;
   if (ctx->kernel_timing) {
     SPD_HIP(hipEventRecord(ps.ev_end, stream));
     ps.timed = true;
