@@ -351,9 +351,16 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
   }
 
   l += __shfl_xor(l, 32);
-  if (wave_active && qi < w.len) {
+  // Output: a lane holds one query row in 8-byte bits, 8 KiB apart from its neighbour's: stored like
+  // that, every store instruction would touch 32 rows 16 bytes at a time.  The K/V stages are free
+  // once every wave is here, so each wave turns its 32 x DV block round in its own piece of LDS and
+  // writes whole rows, 16 bytes per lane.
+  asm volatile("s_barrier" ::: "memory");
+  if (wave_active) {
+    constexpr int OPITCH = DV * 2 + 16;           // bytes per staged row (padded against bank conflicts)
+    constexpr int CPR = DV / 8;                   // 16-byte pieces per row
+    char* ost = smem + wave * (32 * OPITCH);
     const float inv = 1.f / l;
-    bf16_t* op = out + ((size_t)(w.row0 + qi) * H + h) * DV + 4 * hh;
 #pragma unroll
     for (int blk = 0; blk < VB; ++blk)
 #pragma unroll
@@ -361,8 +368,16 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
         uint2 pk;
         pk.x = cvt_pk_bf16(O[blk][4 * i4] * inv, O[blk][4 * i4 + 1] * inv);
         pk.y = cvt_pk_bf16(O[blk][4 * i4 + 2] * inv, O[blk][4 * i4 + 3] * inv);
-        *(uint2*)(op + 32 * blk + 8 * i4) = pk;
+        *(uint2*)(ost + n32 * OPITCH + (32 * blk + 8 * i4 + 4 * hh) * 2) = pk;
       }
+    bf16_t* obase = out + ((size_t)(w.row0 + wave_q0) * H + h) * DV;
+    const int rows = min(32, w.len - wave_q0);
+#pragma unroll
+    for (int it = 0; it < 32 * CPR / 64; ++it) {
+      const int i = lane + 64 * it;
+      const int r = i / CPR, cc = i % CPR;
+      if (r < rows) *(uint4*)(obase + (size_t)r * H * DV + cc * 8) = *(const uint4*)(ost + r * OPITCH + cc * 16);
+    }
   }
 }
 
