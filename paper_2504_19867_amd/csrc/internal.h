@@ -166,8 +166,10 @@ hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const voi
                              const void* d_items, int n_items, int B, int H, float scale, int chunk_steps,
                              int max_chunks, float* ws_o, float* ws_ml, hipStream_t stream);
 int decode_mla_step_tokens();
+// one workgroup per chain: workgroup b computes the items d_work[d_chain[b]] .. d_work[d_chain[b + 1] - 1]
 hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out, const PrefillWork* d_work,
-                          int n_work, int H, int Hkv, int dqk, int dv, float scale, hipStream_t stream);
+                          const int32_t* d_chain, int n_blocks, int H, int Hkv, int dqk, int dv, float scale,
+                          hipStream_t stream);
 // d_pos, d_w may be device-readable pinned host memory
 hipError_t launch_rope(void* q, int n_q_heads, void* k, int n_kv_heads, int dim, int rot, int off, bool interleaved,
                        int n_tokens, const int32_t* d_pos, const double* d_w, hipStream_t stream);

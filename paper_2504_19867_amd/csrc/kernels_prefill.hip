@@ -20,6 +20,11 @@
 // the S^T accumulators are already in the B-operand order of the second product: P never
 // leaves registers.  Q^T fragments live in registers for the whole workgroup.
 //
+// The kernel is persistent: one workgroup per compute unit of the prefill share walks a chain of
+// work items (one item = one tile of query rows of one request for one group of heads), and the
+// K/V tile loads run ahead of the compute across item boundaries, so that an item's first tiles,
+// which a fresh workgroup would have to wait for, arrive while the item before is still computing.
+//
 // K and V tiles of 64 keys stream from global memory straight into a ring of LDS stages with
 // global_load_lds_dwordx4 (no register staging, no LDS stores), PD tiles ahead of the compute;
 // one s_barrier per tile.  K rows are read back with 16-byte reads in A-operand order; V stays
@@ -64,7 +69,8 @@ template <int DV> __device__ inline int v_swz(int row) { return DV == 128 ? 4 * 
 template <int DQK, int DV, int HB>
 __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                          const bf16_t* __restrict__ v, bf16_t* __restrict__ out,
-                                                         const PrefillWork* __restrict__ work, int H, int Hkv,
+                                                         const PrefillWork* __restrict__ work,
+                                                         const int32_t* __restrict__ chain, int H, int Hkv,
                                                          float c /* scale * log2(e) */) {
   constexpr int QS = WAVES / HB;                // 32-row sub-tiles per workgroup
   constexpr int CHK = DQK / 8, CHV = DV / 8;    // 16-byte chunks per K / V row
@@ -76,41 +82,22 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
   constexpr int LPW = NI / WAVES;               // load instructions per wave per tile
   constexpr int KS = DQK / 16, VB = DV / 32;
   constexpr int NS = 2 * KS;                    // MFMAs of S^T
-  constexpr int RING = 8;                       // K operands in flight
+  constexpr int RING = DQK > 128 ? 4 : 8;       // K operands in flight (fewer where registers are short)
   static_assert(NS >= RING, "operand ring longer than the first product");
-  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE_BYTES];
+  constexpr int OPITCH = 32 * 2 + 16;           // bytes per staged output row piece (32 dims, padded)
+  constexpr int EPI_BYTES = WAVES * 32 * OPITCH;  // output staging, apart from the K/V stages
+  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE_BYTES + EPI_BYTES];
 
-  const PrefillWork w = work[blockIdx.x];
-  if (w.len <= 0) return;                       // padding item
   const int G = H / Hkv;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n32 = lane & 31, hh = lane >> 5;
-  const int h = w.head0 + wave % HB;
-  const int g = w.head0 / G;
-  const int q_start = w.q_tile * (32 * QS);
-  const int wave_q0 = q_start + 32 * (wave / HB);
-  const bool wave_active = wave_q0 < w.len;     // waves past the prompt's end only help loading
-  const int qi = wave_q0 + n32;                 // this lane's query (row inside the request)
-  const int qi_c = qi < w.len ? qi : w.len - 1;
-  const int kv_len = w.q_off + w.len;           // cached prefix + this step's rows
-  const int pos0 = w.q_off + wave_q0;           // position of this wave's first query in the request
-  const int pos = w.q_off + qi;                 // ... of this lane's query
-
-  // Q^T fragments (B operand: column = query, 8 consecutive dims per lane and k-step)
-  bf16x8 qf[KS];
-  {
-    const bf16_t* qp = q + ((size_t)(w.row0 + qi_c) * H + h) * DQK + 8 * hh;
-#pragma unroll
-    for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * s));
-  }
-
-  const int kv_end = min(kv_len, w.q_off + q_start + 32 * QS);
-  const int n_kv_tiles = (kv_end + BN - 1) / BN;
-  const char* kbase = (const char*)(k + ((size_t)w.kv_row0 * Hkv + g) * DQK);
-  const char* vbase = (const char*)(v + ((size_t)w.kv_row0 * Hkv + g) * DV);
   const uint32_t k_pitch = (uint32_t)Hkv * DQK * 2, v_pitch = (uint32_t)Hkv * DV * 2;
   const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  // this workgroup's chain of work items
+  int it = __builtin_amdgcn_readfirstlane(chain[blockIdx.x]);
+  const int it_end = __builtin_amdgcn_readfirstlane(chain[blockIdx.x + 1]);
+  if (it >= it_end) return;
 
   // ---- tile loads.  Load instruction ii = wave + 8 j (j < LPW) fills the 64 consecutive 16-byte
   // slots [64 ii, 64 ii + 64) of the stage: K slots first (row = slot / CHK), then V slots.
@@ -138,19 +125,35 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     slot_of(j, row, coff, pitch);
     ld_voff[j] = (uint32_t)row * pitch + (uint32_t)coff;
   }
-  auto issue_loads = [&](int kt) {
-    const int kv0 = kt * BN;
-    const uint32_t stage = smem_base + (uint32_t)(kt % NSTAGE) * STAGE_BYTES;
-    const char* kb = kbase + (size_t)kv0 * k_pitch;
-    const char* vb = vbase + (size_t)kv0 * v_pitch;
-    if (kv0 + BN <= kv_len) {
+  // ---- producer: the tile loads run PD tiles ahead of the compute, across the items of the chain.
+  // pt counts the tiles issued so far (tile number pt goes to stage pt % NSTAGE).
+  int p_it = it, p_kt = 0, p_n = 0, p_kv_len = 0, pt = 0;
+  const char *p_kb = nullptr, *p_vb = nullptr;
+  auto producer_item = [&]() {                  // producer state for item p_it
+    const PrefillWork pw = work[p_it];
+    const int pg = pw.head0 / G;
+    p_kv_len = pw.q_off + pw.len;
+    const int kv_end = min(p_kv_len, pw.q_off + pw.q_tile * (32 * QS) + 32 * QS);
+    p_n = (kv_end + BN - 1) / BN;
+    p_kb = (const char*)(k + ((size_t)pw.kv_row0 * Hkv + pg) * DQK);
+    p_vb = (const char*)(v + ((size_t)pw.kv_row0 * Hkv + pg) * DV);
+    p_kt = 0;
+  };
+  producer_item();
+  auto produce_one = [&]() {
+    if (p_it >= it_end) return;
+    const int kv0 = p_kt * BN;
+    const uint32_t stage = smem_base + (uint32_t)(pt % NSTAGE) * STAGE_BYTES;
+    const char* kb = p_kb + (size_t)kv0 * k_pitch;
+    const char* vb = p_vb + (size_t)kv0 * v_pitch;
+    if (kv0 + BN <= p_kv_len) {
 #pragma unroll
       for (int j = 0; j < LPW; ++j) {
         const int ii = wave + WAVES * j;
         dma16s(ii < CHK ? kb : vb, ld_voff[j], stage + (uint32_t)ii * 1024);
       }
     } else {                                    // rows past the prompt re-read its last row
-      const int last = kv_len - 1 - kv0;
+      const int last = p_kv_len - 1 - kv0;
 #pragma unroll
       for (int j = 0; j < LPW; ++j) {
         const int ii = wave + WAVES * j;
@@ -159,6 +162,11 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
         slot_of(j, row, coff, pitch);
         dma16s(ii < CHK ? kb : vb, (uint32_t)min(row, last) * pitch + (uint32_t)coff, stage + (uint32_t)ii * 1024);
       }
+    }
+    ++pt;
+    if (++p_kt == p_n) {
+      ++p_it;
+      if (p_it < it_end) producer_item();
     }
   };
 
@@ -195,34 +203,86 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
   }
   const uint32_t ones2 = 0x3f803f80u;           // (1.0, 1.0) in bf16
 
+  int ct = 0;                                   // tiles consumed so far (tile number ct sits in stage ct % NSTAGE)
+#pragma unroll
+  for (int t = 0; t < PD; ++t) produce_one();
+
+  // ---- state of the item being computed
+  PrefillWork w;
+  int h = 0, wave_q0 = 0, qi = 0, pos0 = 0, pos = 0, n_kv_tiles = 0, kt = 0;
+  bool wave_active = false;
+  bf16x8 qf[KS];                                // Q^T fragments (B operand: column = query, 8 consecutive dims per lane and k-step)
   f32x16 O[VB];
+  float m = 0.f, l = 0.f;
+  auto item_begin = [&]() {
+    w = work[it];
+    h = w.head0 + wave % HB;
+    const int q_start = w.q_tile * (32 * QS);
+    wave_q0 = q_start + 32 * (wave / HB);
+    wave_active = wave_q0 < w.len;              // waves past the prompt's end only help loading
+    qi = wave_q0 + n32;                         // this lane's query (row inside the request)
+    const int qi_c = qi < w.len ? qi : w.len - 1;
+    const int kv_len = w.q_off + w.len;         // cached prefix + this step's rows
+    pos0 = w.q_off + wave_q0;                   // position of this wave's first query in the request
+    pos = w.q_off + qi;                         // ... of this lane's query
+    const bf16_t* qp = q + ((size_t)(w.row0 + qi_c) * H + h) * DQK + 8 * hh;
 #pragma unroll
-  for (int i = 0; i < VB; ++i)
+    for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * s));
+    const int kv_end = min(kv_len, w.q_off + q_start + 32 * QS);
+    n_kv_tiles = (kv_end + BN - 1) / BN;
+    kt = 0;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) O[i][e] = 0.f;
-  float m = -INFINITY, l = 0.f;
+    for (int i = 0; i < VB; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) O[i][e] = 0.f;
+    m = -INFINITY;
+    l = 0.f;
+    // Draw the compiler's wait for the Q loads to this point.  Left to itself it waits at their first
+    // use, inside the tile, with a count that knows nothing of the tile loads issued by hand.
+#pragma unroll
+    for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(__builtin_bit_cast(uint4, qf[s]).x));
+  };
+  auto item_end = [&]() {
+    l += __shfl_xor(l, 32);
+    // Output: a lane holds one query row in 8-byte bits, 8 KiB apart from its neighbour's.  Each wave
+    // turns its block round, 32 dims at a time, in its own piece of LDS and writes 64-byte row pieces.
+    if (wave_active) {
+      char* ost = smem + NSTAGE * STAGE_BYTES + wave * (32 * OPITCH);
+      const float inv = 1.f / l;
+      bf16_t* obase = out + ((size_t)(w.row0 + wave_q0) * H + h) * DV;
+      const int rows = min(32, w.len - wave_q0);
+#pragma unroll
+      for (int blk = 0; blk < VB; ++blk) {
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          uint2 pk;
+          pk.x = cvt_pk_bf16(O[blk][4 * i4] * inv, O[blk][4 * i4 + 1] * inv);
+          pk.y = cvt_pk_bf16(O[blk][4 * i4 + 2] * inv, O[blk][4 * i4 + 3] * inv);
+          *(uint2*)(ost + n32 * OPITCH + (8 * i4 + 4 * hh) * 2) = pk;
+        }
+#pragma unroll
+        for (int itr = 0; itr < 2; ++itr) {       // 32 rows x 4 pieces of 16 bytes
+          const int i = lane + 64 * itr;
+          const int r = i >> 2, cc = i & 3;
+          if (r < rows) *(uint4*)(obase + (size_t)r * H * DV + 32 * blk + cc * 8) = *(const uint4*)(ost + r * OPITCH + cc * 16);
+        }
+      }
+    }
+  };
 
-#pragma unroll
-  for (int t = 0; t < PD; ++t)
-    if (t < n_kv_tiles) issue_loads(t);
-  // Draw the compiler's wait for the Q loads to this point, after the first tiles are on their
-  // way.  Left to itself it waits at their first use, inside the tile loop, with a count that
-  // knows nothing of the tile loads issued by hand: every iteration would then drain the whole
-  // prefetch queue.
-#pragma unroll
-  for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(__builtin_bit_cast(uint4, qf[s]).x));
-
-  auto tile = [&](auto stc, int kt) {
+  auto tile = [&](auto stc) {
     const int ST = stc;                         // ring stage of tile kt: a constant when the loop is unrolled
     const int kv0 = kt * BN;
     // this wave's loads of tile kt are done when at most (tiles issued after kt) * LPW remain
-    const int later = min(PD - 1, n_kv_tiles - 1 - kt);
+    // this wave's loads of the tile are done when at most (tiles issued after it) * LPW remain
+    const int later = pt - ct - 1;
     if (later >= 2) SPD_WAIT_VMCNT(2 * LPW);
     else if (later == 1) SPD_WAIT_VMCNT(LPW);
     else SPD_WAIT_VMCNT(0);
-    // all waves: tile kt has landed, and everyone is done with tile kt - 1, whose stage is refilled next
+    // all waves: the tile has landed, and everyone is done with the one before, whose stage is refilled next
     asm volatile("s_barrier" ::: "memory");
-    if (kt + PD < n_kv_tiles) issue_loads(kt + PD);
+    produce_one();
+    ++ct;
     if (!wave_active || kv0 > pos0 + 31) return;               // every key of the tile is in this wave's future
 
     const char* sbase = UNROLL ? smem + (ST & 1) * STAGE_BYTES : smem + ST * STAGE_BYTES;
@@ -331,52 +391,30 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
       }
     }
   };
-  if constexpr (UNROLL) {
-    using C0 = std::integral_constant<int, 0>;
-    using C1 = std::integral_constant<int, 1>;
-    using C2 = std::integral_constant<int, 2>;
-    using C3 = std::integral_constant<int, 3>;
-    int kt = 0;
-    for (; kt + 4 <= n_kv_tiles; kt += 4) {
-      tile(C0{}, kt);
-      tile(C1{}, kt + 1);
-      tile(C2{}, kt + 2);
-      tile(C3{}, kt + 3);
-    }
-    if (kt < n_kv_tiles) tile(C0{}, kt);
-    if (kt + 1 < n_kv_tiles) tile(C1{}, kt + 1);
-    if (kt + 2 < n_kv_tiles) tile(C2{}, kt + 2);
-  } else {
-    for (int kt = 0; kt < n_kv_tiles; ++kt) tile(kt % NSTAGE, kt);
-  }
 
-  l += __shfl_xor(l, 32);
-  // Output: a lane holds one query row in 8-byte bits, 8 KiB apart from its neighbour's: stored like
-  // that, every store instruction would touch 32 rows 16 bytes at a time.  The K/V stages are free
-  // once every wave is here, so each wave turns its 32 x DV block round in its own piece of LDS and
-  // writes whole rows, 16 bytes per lane.
-  asm volatile("s_barrier" ::: "memory");
-  if (wave_active) {
-    constexpr int OPITCH = DV * 2 + 16;           // bytes per staged row (padded against bank conflicts)
-    constexpr int CPR = DV / 8;                   // 16-byte pieces per row
-    char* ost = smem + wave * (32 * OPITCH);
-    const float inv = 1.f / l;
-#pragma unroll
-    for (int blk = 0; blk < VB; ++blk)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        uint2 pk;
-        pk.x = cvt_pk_bf16(O[blk][4 * i4] * inv, O[blk][4 * i4 + 1] * inv);
-        pk.y = cvt_pk_bf16(O[blk][4 * i4 + 2] * inv, O[blk][4 * i4 + 3] * inv);
-        *(uint2*)(ost + n32 * OPITCH + (32 * blk + 8 * i4 + 4 * hh) * 2) = pk;
-      }
-    bf16_t* obase = out + ((size_t)(w.row0 + wave_q0) * H + h) * DV;
-    const int rows = min(32, w.len - wave_q0);
-#pragma unroll
-    for (int it = 0; it < 32 * CPR / 64; ++it) {
-      const int i = lane + 64 * it;
-      const int r = i / CPR, cc = i % CPR;
-      if (r < rows) *(uint4*)(obase + (size_t)r * H * DV + cc * 8) = *(const uint4*)(ost + r * OPITCH + cc * 16);
+
+  // one tile of the chain; false when the chain is finished
+  auto step = [&](auto stc) -> bool {
+    tile(stc);
+    if (++kt == n_kv_tiles) {
+      item_end();
+      if (++it >= it_end) return false;
+      item_begin();
+    }
+    return true;
+  };
+  item_begin();
+  if constexpr (UNROLL) {
+    // the ring's stages in turn, each with its LDS offsets as immediates; items follow one another
+    // without a break in the ring
+    for (;;) {
+      if (!step(std::integral_constant<int, 0>{})) break;
+      if (!step(std::integral_constant<int, 1>{})) break;
+      if (!step(std::integral_constant<int, 2>{})) break;
+      if (!step(std::integral_constant<int, 3>{})) break;
+    }
+  } else {
+    while (step(ct % NSTAGE)) {
     }
   }
 }
@@ -395,23 +433,23 @@ int prefill_block_m(int group) { return 32 * (WAVES / prefill_heads_per_block(gr
 
 template <int DQK, int DV>
 static void launch_hb(int hb, dim3 grid, hipStream_t stream, const bf16_t* q, const bf16_t* k, const bf16_t* v,
-                      bf16_t* out, const PrefillWork* work, int H, int Hkv, float c) {
+                      bf16_t* out, const PrefillWork* work, const int32_t* chain, int H, int Hkv, float c) {
   const dim3 block(64 * WAVES);
-  if (hb == 8) hipLaunchKernelGGL((prefill_kernel<DQK, DV, 8>), grid, block, 0, stream, q, k, v, out, work, H, Hkv, c);
-  else if (hb == 4) hipLaunchKernelGGL((prefill_kernel<DQK, DV, 4>), grid, block, 0, stream, q, k, v, out, work, H, Hkv, c);
-  else if (hb == 2) hipLaunchKernelGGL((prefill_kernel<DQK, DV, 2>), grid, block, 0, stream, q, k, v, out, work, H, Hkv, c);
-  else hipLaunchKernelGGL((prefill_kernel<DQK, DV, 1>), grid, block, 0, stream, q, k, v, out, work, H, Hkv, c);
+  if (hb == 8) hipLaunchKernelGGL((prefill_kernel<DQK, DV, 8>), grid, block, 0, stream, q, k, v, out, work, chain, H, Hkv, c);
+  else if (hb == 4) hipLaunchKernelGGL((prefill_kernel<DQK, DV, 4>), grid, block, 0, stream, q, k, v, out, work, chain, H, Hkv, c);
+  else if (hb == 2) hipLaunchKernelGGL((prefill_kernel<DQK, DV, 2>), grid, block, 0, stream, q, k, v, out, work, chain, H, Hkv, c);
+  else hipLaunchKernelGGL((prefill_kernel<DQK, DV, 1>), grid, block, 0, stream, q, k, v, out, work, chain, H, Hkv, c);
 }
 
-hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out, const PrefillWork* d_work, int n_work,
-                          int H, int Hkv, int dqk, int dv, float scale, hipStream_t stream) {
+hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out, const PrefillWork* d_work,
+                          const int32_t* d_chain, int n_blocks, int H, int Hkv, int dqk, int dv, float scale, hipStream_t stream) {
   const float c = scale * 1.4426950408889634f;
   const int hb = prefill_heads_per_block(H / Hkv);
-  const dim3 grid((unsigned)n_work);
+  const dim3 grid((unsigned)n_blocks);
   const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v;
-  if (dqk == 64 && dv == 64) launch_hb<64, 64>(hb, grid, stream, qq, kk, vv, (bf16_t*)out, d_work, H, Hkv, c);
-  else if (dqk == 128 && dv == 128) launch_hb<128, 128>(hb, grid, stream, qq, kk, vv, (bf16_t*)out, d_work, H, Hkv, c);
-  else if (dqk == 192 && dv == 128) launch_hb<192, 128>(hb, grid, stream, qq, kk, vv, (bf16_t*)out, d_work, H, Hkv, c);
+  if (dqk == 64 && dv == 64) launch_hb<64, 64>(hb, grid, stream, qq, kk, vv, (bf16_t*)out, d_work, d_chain, H, Hkv, c);
+  else if (dqk == 128 && dv == 128) launch_hb<128, 128>(hb, grid, stream, qq, kk, vv, (bf16_t*)out, d_work, d_chain, H, Hkv, c);
+  else if (dqk == 192 && dv == 128) launch_hb<192, 128>(hb, grid, stream, qq, kk, vv, (bf16_t*)out, d_work, d_chain, H, Hkv, c);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

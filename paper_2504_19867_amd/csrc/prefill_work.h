@@ -1,4 +1,4 @@
-// Host-side work list of the prefill kernel: which workgroup does what, and in which order.
+// Host-side work list of the persistent prefill kernel: items, and one chain of items per workgroup.
 #pragma once
 
 #include <algorithm>
@@ -8,18 +8,23 @@
 
 namespace spd {
 
-// Workgroups are dispatched round-robin over the XCDs (workgroup i runs on XCD i % xcds), and each
-// XCD has its own L2.  All workgroups that read the same K, V - the query tiles and head groups of
-// one (request, KV head) "unit" - are therefore queued on the same XCD, one unit after the other,
-// so that a unit's K, V is fetched into one L2 only and stays hot while its tiles run.  Inside a
-// unit the causally heaviest tiles (largest tile index) go first.  Units are spread over the XCDs
-// longest-first; with fewer units than XCDs the tiles themselves are dealt round-robin.
-// prefix_lens (may be null): tokens of each request that precede its query rows; its keys / values
-// then start at row kv_cu[r] of the K, V tensors (prefix + len rows per request), else at row0.
-inline void build_prefill_work(const int32_t* cu_seqlens, const int32_t* prefix_lens, const int32_t* kv_cu, int n_req,
-                               int H, int Hkv, int xcds, std::vector<PrefillWork>& out) {
+// One workgroup per compute unit walks a chain of work items.  Workgroup b runs on XCD b % xcds
+// (round-robin dispatch), and each XCD has its own L2, so all items that read the same K, V - the
+// query tiles and head groups of one (request, KV head) "unit" - go to chains of the same XCD.
+// Units are spread over the XCDs longest-first; inside an XCD the items are dealt longest-first onto
+// the least-loaded chain (weight = KV tiles to visit + a fixed per-item cost), and every chain is
+// ordered by unit, so that the chains of an XCD work on the same unit at about the same time.
+// With fewer units than XCDs the items themselves are dealt round-robin.
+// n_blocks == 0 asks for one workgroup per item instead (chains of length one, handed out by the
+// hardware in launch order: the XCDs' queues interleaved, each queue heaviest unit first): for
+// partitions on which a launch of exactly one workgroup per compute unit does not get one compute
+// unit each.
+inline void build_prefill_chains(const int32_t* cu_seqlens, const int32_t* prefix_lens, const int32_t* kv_cu, int n_req,
+                                 int H, int Hkv, int xcds, int n_blocks, std::vector<PrefillWork>& work,
+                                 std::vector<int32_t>& chain) {
   const int G = H / Hkv, hb = prefill_heads_per_block(G), bm = prefill_block_m(G), groups = G / hb;
-  struct Unit { long weight; std::vector<PrefillWork> items; };
+  struct Item { PrefillWork w; long weight; int unit; };
+  struct Unit { long weight; std::vector<Item> items; };
   std::vector<Unit> units;
   for (int r = 0; r < n_req; ++r) {
     const int32_t row0 = cu_seqlens[r], len = cu_seqlens[r + 1] - row0;
@@ -29,33 +34,80 @@ inline void build_prefill_work(const int32_t* cu_seqlens, const int32_t* prefix_
       Unit u{0, {}};
       for (int t = tiles - 1; t >= 0; --t)
         for (int hg = 0; hg < groups; ++hg) {
-          u.items.push_back(PrefillWork{row0, len, t, g * G + hg * hb, kv_row0, q_off});
-          u.weight += q_off + std::min<long>(len, (long)(t + 1) * bm);
+          const long kv_tiles = (q_off + std::min<long>(len, (long)(t + 1) * bm) + 63) / 64;
+          u.items.push_back(Item{PrefillWork{row0, len, t, g * G + hg * hb, kv_row0, q_off}, kv_tiles + 1, (int)units.size()});
+          u.weight += kv_tiles + 1;
         }
       units.push_back(std::move(u));
     }
   }
-  std::vector<std::vector<PrefillWork>> queue((size_t)xcds);
+  if (n_blocks == 0) {
+    std::vector<std::vector<PrefillWork>> queue((size_t)xcds);
+    if ((int)units.size() >= xcds) {
+      std::vector<long> load((size_t)xcds, 0);
+      std::vector<size_t> order(units.size());
+      for (size_t i = 0; i < order.size(); ++i) order[i] = i;
+      std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return units[a].weight > units[b].weight; });
+      for (size_t ui : order) {
+        const int x = (int)(std::min_element(load.begin(), load.end()) - load.begin());
+        load[(size_t)x] += units[ui].weight;
+        for (const Item& it : units[ui].items) queue[(size_t)x].push_back(it.w);
+      }
+    } else {
+      size_t n = 0;
+      for (Unit& u : units)
+        for (Item& it : u.items) queue[n++ % (size_t)xcds].push_back(it.w);
+    }
+    size_t longest = 0;
+    for (auto& qv : queue) longest = std::max(longest, qv.size());
+    work.clear();
+    chain.clear();
+    for (size_t i = 0; i < longest; ++i)
+      for (int x = 0; x < xcds; ++x) {          // workgroup i * xcds + x runs on XCD x
+        chain.push_back((int32_t)work.size());
+        if (i < queue[(size_t)x].size()) work.push_back(queue[(size_t)x][i]);
+      }
+    chain.push_back((int32_t)work.size());
+    return;
+  }
+  if (n_blocks < xcds || n_blocks % xcds) xcds = 1;
+  const int per_xcd = n_blocks / xcds;            // chains per XCD
+  std::vector<std::vector<Item>> xq((size_t)xcds);
   if ((int)units.size() >= xcds) {
     std::vector<long> load((size_t)xcds, 0);
-    std::stable_sort(units.begin(), units.end(), [](const Unit& a, const Unit& b) { return a.weight > b.weight; });
-    for (Unit& u : units) {
+    std::vector<size_t> order(units.size());
+    for (size_t i = 0; i < order.size(); ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return units[a].weight > units[b].weight; });
+    for (size_t ui : order) {
       const int x = (int)(std::min_element(load.begin(), load.end()) - load.begin());
-      load[(size_t)x] += u.weight;
-      queue[(size_t)x].insert(queue[(size_t)x].end(), u.items.begin(), u.items.end());
+      load[(size_t)x] += units[ui].weight;
+      xq[(size_t)x].insert(xq[(size_t)x].end(), units[ui].items.begin(), units[ui].items.end());
     }
   } else {
     size_t n = 0;
     for (Unit& u : units)
-      for (PrefillWork& w : u.items) queue[n++ % (size_t)xcds].push_back(w);
+      for (Item& it : u.items) xq[n++ % (size_t)xcds].push_back(it);
   }
-  size_t longest = 0;
-  for (auto& qv : queue) longest = std::max(longest, qv.size());
-  out.clear();
-  out.reserve(longest * (size_t)xcds);
-  for (size_t i = 0; i < longest; ++i)
-    for (int x = 0; x < xcds; ++x)
-      out.push_back(i < queue[(size_t)x].size() ? queue[(size_t)x][i] : PrefillWork{0, 0, 0, 0, 0, 0});
+  std::vector<std::vector<Item>> chains((size_t)n_blocks);
+  for (int x = 0; x < xcds; ++x) {
+    std::vector<Item>& items = xq[(size_t)x];
+    std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.weight > b.weight; });
+    std::vector<long> load((size_t)per_xcd, 0);
+    for (const Item& it : items) {
+      const int c = (int)(std::min_element(load.begin(), load.end()) - load.begin());
+      load[(size_t)c] += it.weight;
+      chains[(size_t)(c * xcds + x)].push_back(it);          // workgroup id = chain slot * xcds + xcd
+    }
+  }
+  work.clear();
+  chain.assign((size_t)n_blocks + 1, 0);
+  for (int b = 0; b < n_blocks; ++b) {
+    std::vector<Item>& ch = chains[(size_t)b];
+    std::stable_sort(ch.begin(), ch.end(), [](const Item& a, const Item& c) { return a.unit < c.unit; });
+    chain[(size_t)b] = (int32_t)work.size();
+    for (const Item& it : ch) work.push_back(it.w);
+  }
+  chain[(size_t)n_blocks] = (int32_t)work.size();
 }
 
 }  // namespace spd

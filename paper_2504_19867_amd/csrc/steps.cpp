@@ -123,13 +123,22 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
     }
   }
 
-  std::vector<PrefillWork> work;
-  build_prefill_work(b->cu_seqlens, chunked ? b->prefix_lens : nullptr, chunked ? kv_cu.data() : nullptr, b->n_req,
-                     b->n_q_heads, b->n_kv_heads, ctx->xcds, work);
-
   hipStream_t stream;
   int rc = phase_enter(ctx, SPD_PHASE_PREFILL, &stream);
   if (rc != SPD_OK) return rc;
+  // One persistent workgroup per compute unit of the prefill share, each with its chain of work
+  // items, where such a launch gets one compute unit per workgroup: measured so when every XCD
+  // contributes a multiple of 8 compute units (whole shader arrays), not otherwise (80 or 176 compute
+  // units: some workgroups then wait for others to finish, and the step takes up to twice as
+  // long).  Elsewhere: one workgroup per item, handed out by the hardware as compute units free up.
+  const int share = std::max(1, ctx->phase[SPD_PHASE_PREFILL].active_cus);
+  bool persistent = share % ctx->xcds == 0 && (share / ctx->xcds) % 8 == 0;
+  if (const char* env = getenv("SPD_PREFILL_PERSISTENT")) persistent = atoi(env) != 0;   // experiment switch, read per call
+  std::vector<PrefillWork> work;
+  std::vector<int32_t> chain;
+  build_prefill_chains(b->cu_seqlens, chunked ? b->prefix_lens : nullptr, chunked ? kv_cu.data() : nullptr, b->n_req,
+                       b->n_q_heads, b->n_kv_heads, ctx->xcds, persistent ? share : 0, work, chain);
+  const int n_blocks = (int)chain.size() - 1;
 
   size_t n_descs = 0, n_gather = 0;
   for (int r = 0; r < b->n_req; ++r) {
@@ -137,7 +146,8 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
     n_descs += (size_t)((pre % TILE_T) + len + TILE_T - 1) / TILE_T;
     if (chunked) n_gather += (size_t)(pre + len + TILE_T - 1) / TILE_T;
   }
-  size_t off_desc = align16(work.size() * sizeof(PrefillWork));
+  size_t off_chain = align16(work.size() * sizeof(PrefillWork));
+  size_t off_desc = align16(off_chain + chain.size() * sizeof(int32_t));
   size_t off_gather = align16(off_desc + n_descs * sizeof(TileDesc));
   size_t bytes = off_gather + n_gather * sizeof(TileDesc);
   spd_stage* st;
@@ -174,6 +184,7 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
     }
   }
   memcpy(st->host, work.data(), work.size() * sizeof(PrefillWork));
+  memcpy(st->host + off_chain, chain.data(), chain.size() * sizeof(int32_t));
   memcpy(st->host + off_desc, descs.data(), descs.size() * sizeof(TileDesc));
   if (chunked) memcpy(st->host + off_gather, gdescs.data(), gdescs.size() * sizeof(TileDesc));
   spd_phase_state& ps = ctx->phase[SPD_PHASE_PREFILL];
@@ -196,8 +207,8 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
     att_v = ws + ws_k_bytes;
   }
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_PREFILL, 0, stream)) != SPD_OK) return rc;
-  SPD_HIP(launch_prefill(b->q, att_k, att_v, b->out, (const PrefillWork*)st->dev, (int)work.size(), b->n_q_heads,
-                         b->n_kv_heads, b->dim_qk, b->dim_v, b->scale, stream));
+  SPD_HIP(launch_prefill(b->q, att_k, att_v, b->out, (const PrefillWork*)st->dev, (const int32_t*)(st->dev + off_chain),
+                         n_blocks, b->n_q_heads, b->n_kv_heads, b->dim_qk, b->dim_v, b->scale, stream));
   if ((rc = kernel_timing_mark(ctx, SPD_PHASE_PREFILL, 1, stream)) != SPD_OK) return rc;
   // the staging buffer is free again once the kernels above have run; its event goes behind the
   // attention kernel so that nothing sits between the page write and the attention launch
