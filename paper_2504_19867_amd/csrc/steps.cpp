@@ -131,8 +131,21 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   // contributes a multiple of 8 compute units (whole shader arrays), not otherwise (80 or 176 compute
   // units: some workgroups then wait for others to finish, and the step takes up to twice as
   // long).  Elsewhere: one workgroup per item, handed out by the hardware as compute units free up.
+  // Nor where the two phases' masks overlap: a persistent workgroup keeps its compute unit for the
+  // whole kernel, and decode workgroups that are allowed nowhere else would wait that long.
   const int share = std::max(1, ctx->phase[SPD_PHASE_PREFILL].active_cus);
   bool persistent = share % ctx->xcds == 0 && (share / ctx->xcds) % 8 == 0;
+  {
+    std::lock_guard<std::mutex> lk(ctx->part_mu);
+    const std::vector<uint32_t>& pm = ctx->phase[SPD_PHASE_PREFILL].active_mask;
+    const spd_phase_state& dsx = ctx->phase[SPD_PHASE_DECODE];
+    const std::vector<uint32_t>& dm = dsx.has_pending ? dsx.pending_mask : dsx.active_mask;
+    for (size_t i = 0; i < pm.size() && i < dm.size(); ++i)
+      if (pm[i] & dm[i]) persistent = false;
+    if (dsx.has_pending)
+      for (size_t i = 0; i < pm.size() && i < dsx.active_mask.size(); ++i)
+        if (pm[i] & dsx.active_mask[i]) persistent = false;
+  }
   if (const char* env = getenv("SPD_PREFILL_PERSISTENT")) persistent = atoi(env) != 0;   // experiment switch, read per call
   std::vector<PrefillWork> work;
   std::vector<int32_t> chain;
