@@ -225,7 +225,8 @@ class Bench:
 def run_async(bench, steps, timing=False):
     """The paper's two asynchronous workers: this thread drives `steps` prefill steps back to back while the
     library's decode worker thread drives decode steps as fast as the decode partition takes them.  Returns wall
-    ms per prefill step (until both partitions have drained), the number of decode steps, the kernel ms lists."""
+    ms per prefill step (K steps, from the first call to the prefill partition's drain, the decode worker running
+    throughout), the number of decode steps issued meanwhile, the kernel ms lists."""
     torch = bench.torch
     bench.sync()
     bench.ctx.set_kernel_timing(timing)
@@ -233,15 +234,24 @@ def run_async(bench, steps, timing=False):
     torch.cuda.synchronize()
     gc.collect()
     gc.disable()                        # keep the Python driver's collector out of the timed region
-    t0 = time.perf_counter()
+    # both workers are running before the clock starts (the decode worker's thread start-up is not part of a
+    # step); the decode steps of the timed region are those issued between its two ends
     worker = bench.pool.decode_worker_start(bench.dec_batches)
+    for _ in range(4):
+        bench.prefill()
+    while bench.pool.decode_worker_steps(worker) < 4:
+        time.sleep(0.0005)
+    bench.ctx.phase_sync(PRE)
+    n0 = bench.pool.decode_worker_steps(worker)
+    t0 = time.perf_counter()
     for _ in range(steps):
         bench.prefill()
     bench.ctx.phase_sync(PRE)
-    n_dec = bench.pool.decode_worker_stop(worker)
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    n_dec = bench.pool.decode_worker_steps(worker) - n0
+    bench.pool.decode_worker_stop(worker)
     bench.ctx.phase_sync(DEC)
     torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     gc.enable()
     pk, dk = bench.ctx.phase_kernel_ms(PRE), bench.ctx.phase_kernel_ms(DEC)
     bench.ctx.set_kernel_timing(False)

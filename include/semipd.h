@@ -249,6 +249,8 @@ typedef struct spd_worker spd_worker;
 int spd_decode_worker_start(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* const* batches, int32_t n_batches,
                             spd_worker** out);
 int spd_decode_worker_stop(spd_worker* w, int64_t* steps_issued, int* status);
+/* Decode steps the running worker has issued so far (a counter read, no synchronisation). */
+int spd_decode_worker_steps(spd_worker* w, int64_t* steps_issued);
 
 /* Block the calling thread until everything enqueued so far by `phase` has finished. */
 int spd_phase_sync(spd_ctx* ctx, int phase);

@@ -458,6 +458,12 @@ extern "C" int spd_decode_worker_start(spd_ctx* ctx, spd_pool* pool, const spd_d
   return SPD_OK;
 }
 
+extern "C" int spd_decode_worker_steps(spd_worker* w, int64_t* steps_issued) {
+  if (!w || !steps_issued) return SPD_EINVAL;
+  *steps_issued = w->issued.load(std::memory_order_relaxed);
+  return SPD_OK;
+}
+
 extern "C" int spd_decode_worker_stop(spd_worker* w, int64_t* steps_issued, int* status) {
   if (!w) return SPD_EINVAL;
   w->stop.store(true);

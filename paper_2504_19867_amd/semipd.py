@@ -28,7 +28,7 @@ EXPORTS = [
     "spd_phase_sync", "spd_phase_query", "spd_phase_wait_for", "spd_phase_stream", "spd_phase_last_ms",
     "spd_set_partition", "spd_get_partition", "spd_phase_cu_mask", "spd_partition_masks",
     "spd_phase_probe_cus", "spd_strerror", "spd_last_hip_error", "spd_set_kernel_timing", "spd_phase_kernel_ms", "spd_phase_copy",
-    "spd_decode_worker_start", "spd_decode_worker_stop",
+    "spd_decode_worker_start", "spd_decode_worker_stop", "spd_decode_worker_steps",
     "spd_ctrl_create", "spd_ctrl_destroy", "spd_ctrl_observe_ttft", "spd_ctrl_observe_tpot", "spd_ctrl_step", "spd_ctrl_model",
     "spd_rope_inv_freq", "spd_rope_qk",
 ]
@@ -116,6 +116,7 @@ def _load() -> C.CDLL:
         "spd_phase_kernel_ms": [vp, C.c_int, P(C.c_float), i32, P(i32)],
         "spd_decode_worker_start": [vp, vp, P(P(spd_decode_batch)), i32, P(vp)],
         "spd_decode_worker_stop": [vp, P(i64), P(C.c_int)],
+        "spd_decode_worker_steps": [vp, P(i64)],
         "spd_ctrl_create": [P(spd_ctrl_config), P(vp)],
         "spd_ctrl_destroy": [vp],
         "spd_ctrl_observe_ttft": [vp, C.c_double],
@@ -400,6 +401,12 @@ class Pool:
         h = C.c_void_p()
         _check(lib.spd_decode_worker_start(self.ctx.h, self.h, arr, n, C.byref(h)), "spd_decode_worker_start")
         return (h, arr, list(batches))
+
+    def decode_worker_steps(self, worker) -> int:
+        """Decode steps the running worker has issued so far."""
+        steps = C.c_int64()
+        _check(lib.spd_decode_worker_steps(worker[0], C.byref(steps)), "spd_decode_worker_steps")
+        return steps.value
 
     def decode_worker_stop(self, worker) -> int:
         """Stop and join the worker; returns the number of decode steps it issued (raises on a failed step)."""
