@@ -129,7 +129,7 @@ struct spd_phase_state {
 
 struct spd_ctx {
   int device = -1;                     // -1: host only
-  int total_cus = 256, xcds = 8, granularity = 8;
+  int total_cus = 256, xcds = 8, granularity = 32;
   std::mutex part_mu;                  // partition state (set_partition vs step entry)
   std::map<std::vector<uint32_t>, hipStream_t> stream_cache;
   spd_phase_state phase[2];

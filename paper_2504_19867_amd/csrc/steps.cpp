@@ -127,14 +127,15 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   int rc = phase_enter(ctx, SPD_PHASE_PREFILL, &stream);
   if (rc != SPD_OK) return rc;
   // One persistent workgroup per compute unit of the prefill share, each with its chain of work
-  // items, where such a launch gets one compute unit per workgroup: measured so when every XCD
-  // contributes a multiple of 8 compute units (whole shader arrays), not otherwise (80 or 176 compute
-  // units: some workgroups then wait for others to finish, and the step takes up to twice as
-  // long).  Elsewhere: one workgroup per item, handed out by the hardware as compute units free up.
+  // items, where such a launch gets one compute unit per workgroup: an XCD deals its workgroups to
+  // its four shader arrays in turn, so every XCD must contribute a multiple of 4 compute units (the
+  // partition granularity sees to that; with 10 per XCD some workgroups wait for others to finish,
+  // and the step takes up to twice as long).  Elsewhere: one workgroup per item, handed out by the
+  // hardware as compute units free up.
   // Nor where the two phases' masks overlap: a persistent workgroup keeps its compute unit for the
   // whole kernel, and decode workgroups that are allowed nowhere else would wait that long.
   const int share = std::max(1, ctx->phase[SPD_PHASE_PREFILL].active_cus);
-  bool persistent = share % ctx->xcds == 0 && (share / ctx->xcds) % 8 == 0;
+  bool persistent = share % ctx->xcds == 0 && (share / ctx->xcds) % 4 == 0;
   {
     std::lock_guard<std::mutex> lk(ctx->part_mu);
     const std::vector<uint32_t>& pm = ctx->phase[SPD_PHASE_PREFILL].active_mask;

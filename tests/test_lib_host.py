@@ -204,11 +204,11 @@ def test_partition_masks_oversubscription_overlaps():
 
 def test_host_only_context_stages_partition_and_refuses_gpu_work():
     ctx, pool = host_pool(16, 16)
-    assert ctx.device_info() == (256, 8, 8)
+    assert ctx.device_info() == (256, 8, 32)
     assert ctx.get_partition() == (256, 256, 256, 256)
     ctx.set_partition(102, 154)
     # delayed switching: staged, not adopted until the phase's next step
-    assert ctx.get_partition() == (256, 256, 104, 152)
+    assert ctx.get_partition() == (256, 256, 96, 160)
     assert bits(ctx.phase_cu_mask(S.SPD_PHASE_PREFILL)) == set(range(256))
     pool.kv_reserve(1, 16)
     for fn in (lambda: ctx.phase_sync(0), lambda: ctx.phase_stream(1), lambda: pool.kv_write(0, 1, 0, 4, 4096, 4096),
