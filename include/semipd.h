@@ -238,6 +238,29 @@ int spd_rope_inv_freq(const spd_rope_config* cfg, double* out, int32_t cap);
 int spd_rope_qk(spd_ctx* ctx, int phase, const spd_rope_config* cfg, const int32_t* positions, int32_t n_tokens,
                 void* q, int32_t n_q_heads, void* k, int32_t n_kv_heads, int32_t dim);
 
+/* ------------------------------------------------------------------ the step after attention */
+
+/* First step of the gated FFN (paper, Evaluation, "Implementation based on DistServe": the first
+ * two GEMMs of the gated FFN are fused into one).  The paper gives no formula; this is the
+ * published gated (SwiGLU) FFN of the Llama models:
+ *     g = x W_gate^T,  u = x W_up^T,  out = silu(g) * u,  silu(z) = z / (1 + exp(-z))
+ * computed as ONE product of x with the joint matrix w_gu [2 inter, hidden], whose rows
+ * 64 b .. 64 b + 31 are rows 32 b .. 32 b + 31 of W_gate and rows 64 b + 32 .. 64 b + 63 the rows
+ * with the same numbers of W_up (so that a gate column and its up column meet in one wave), with the
+ * activation applied to the fp32 accumulators and one rounding to bf16 (nearest even) at the end.
+ * x device [n_tokens, hidden], w_gu device [2 inter, hidden], out device [n_tokens, inter], bf16,
+ * row-major; x and w_gu 16-byte aligned; hidden a multiple of 32, inter a multiple of 128;
+ * n_tokens >= 0 (0: nothing is enqueued).  Enqueued on `phase`'s current stream, i.e. on that
+ * phase's compute units; the buffers belong to the caller and must stay valid until the stream
+ * has run the call.  SPD_EINVAL on any violated condition, nothing enqueued. */
+int spd_ffn_gate_up(spd_ctx* ctx, int phase, const void* x, const void* w_gu, void* out, int32_t n_tokens,
+                    int32_t hidden, int32_t inter);
+/* Builds the joint matrix w_gu device [2 inter, hidden] from w_gate, w_up device [inter, hidden]
+ * (bf16, 16-byte aligned, same conditions on hidden and inter; a copy, done once per layer at load
+ * time).  Enqueued on `phase`'s current stream. */
+int spd_ffn_pack_gate_up(spd_ctx* ctx, int phase, const void* w_gate, const void* w_up, void* w_gu, int32_t hidden,
+                         int32_t inter);
+
 /* A decode worker inside the library (paper, System Design, "Prefill and Decode Workers": the
  * decode worker runs its iterations asynchronously beside the prefill worker).  Starts a host
  * thread that calls spd_decode_step on batches[0], batches[1], ... batches[n_batches-1],

@@ -170,6 +170,10 @@ int decode_mla_step_tokens();
 hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out, const PrefillWork* d_work,
                           const int32_t* d_chain, int n_blocks, int H, int Hkv, int dqk, int dv, float scale,
                           hipStream_t stream);
+// x [T, K], w_gu [2 I, K] (joint gate/up rows in blocks of 32 + 32), out [T, I], all bf16 in device memory;
+// K a multiple of 32, I a multiple of 128
+hipError_t launch_ffn_gate_up(const void* x, const void* w_gu, void* out, int T, int K, int I, int xcds, hipStream_t stream);
+hipError_t launch_ffn_pack(const void* w_gate, const void* w_up, void* w_gu, int K, int I, hipStream_t stream);
 // d_pos, d_w may be device-readable pinned host memory
 hipError_t launch_rope(void* q, int n_q_heads, void* k, int n_kv_heads, int dim, int rot, int off, bool interleaved,
                        int n_tokens, const int32_t* d_pos, const double* d_w, hipStream_t stream);

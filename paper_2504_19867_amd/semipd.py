@@ -30,7 +30,7 @@ EXPORTS = [
     "spd_phase_probe_cus", "spd_strerror", "spd_last_hip_error", "spd_set_kernel_timing", "spd_phase_kernel_ms", "spd_phase_copy",
     "spd_decode_worker_start", "spd_decode_worker_stop", "spd_decode_worker_steps",
     "spd_ctrl_create", "spd_ctrl_destroy", "spd_ctrl_observe_ttft", "spd_ctrl_observe_tpot", "spd_ctrl_step", "spd_ctrl_model",
-    "spd_rope_inv_freq", "spd_rope_qk",
+    "spd_rope_inv_freq", "spd_rope_qk", "spd_ffn_gate_up", "spd_ffn_pack_gate_up",
 ]
 
 
@@ -125,6 +125,8 @@ def _load() -> C.CDLL:
         "spd_ctrl_model": [vp, P(C.c_double)],
         "spd_rope_inv_freq": [P(spd_rope_config), P(C.c_double), i32],
         "spd_rope_qk": [vp, C.c_int, P(spd_rope_config), P(i32), i32, vp, i32, vp, i32, i32],
+        "spd_ffn_gate_up": [vp, C.c_int, vp, vp, vp, i32, i32, i32],
+        "spd_ffn_pack_gate_up": [vp, C.c_int, vp, vp, vp, i32, i32],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -240,6 +242,14 @@ class Context:
         n = len(positions)
         pos = (C.c_int32 * max(n, 1))(*positions)
         _check(lib.spd_rope_qk(self.h, phase, C.byref(cfg), pos, n, _ptr(q), n_q_heads, _ptr(k), n_kv_heads, dim), "spd_rope_qk")
+
+    def ffn_gate_up(self, phase: int, x, w_gu, out, n_tokens: int, hidden: int, inter: int) -> None:
+        """out [T, inter] = silu(x W_gate^T) * (x W_up^T) from the joint matrix w_gu [2 inter, hidden], on `phase`'s stream."""
+        _check(lib.spd_ffn_gate_up(self.h, phase, _ptr(x), _ptr(w_gu), _ptr(out), n_tokens, hidden, inter), "spd_ffn_gate_up")
+
+    def ffn_pack_gate_up(self, phase: int, w_gate, w_up, w_gu, hidden: int, inter: int) -> None:
+        """The joint matrix [2 inter, hidden] (blocks of 32 gate rows + their 32 up rows) from the two weight matrices."""
+        _check(lib.spd_ffn_pack_gate_up(self.h, phase, _ptr(w_gate), _ptr(w_up), _ptr(w_gu), hidden, inter), "spd_ffn_pack_gate_up")
 
     def set_kernel_timing(self, on: bool) -> None:
         _check(lib.spd_set_kernel_timing(self.h, int(on)), "spd_set_kernel_timing")

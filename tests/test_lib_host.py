@@ -350,3 +350,19 @@ def test_rope_argument_checks():
     # the device call: every violated condition is refused before anything is enqueued (a null context too)
     pos = (C.c_int32 * 4)(0, 1, 2, 3)
     assert S.lib.spd_rope_qk(None, 0, C.byref(ok), pos, 4, 16, 2, None, 0, 64) == S.SPD_EINVAL
+
+
+def test_ffn_argument_checks_on_a_host_only_context():
+    ctx, pool = host_pool(16, 16)
+    lib = S.lib
+    bad = [(31, 128), (64, 100), (0, 128), (64, 0), (64, -128)]
+    for hidden, inter in bad:
+        assert lib.spd_ffn_gate_up(ctx.h, 0, 4096, 4096, 4096, 4, hidden, inter) == S.SPD_EINVAL
+        assert lib.spd_ffn_pack_gate_up(ctx.h, 0, 4096, 4096, 4096, hidden, inter) == S.SPD_EINVAL
+    assert lib.spd_ffn_gate_up(ctx.h, 2, 4096, 4096, 4096, 4, 64, 128) == S.SPD_EINVAL          # no such phase
+    assert lib.spd_ffn_gate_up(ctx.h, 0, 4096, 4096, 4096, -1, 64, 128) == S.SPD_EINVAL
+    assert lib.spd_ffn_gate_up(ctx.h, 0, 4100, 4096, 4096, 4, 64, 128) == S.SPD_EINVAL          # x not 16-byte aligned
+    assert lib.spd_ffn_gate_up(ctx.h, 0, None, 4096, 4096, 4, 64, 128) == S.SPD_EINVAL
+    # well-formed, but this context has no device
+    assert lib.spd_ffn_gate_up(ctx.h, 0, 4096, 4096, 4096, 4, 64, 128) == S.SPD_ESTATE
+    assert lib.spd_ffn_pack_gate_up(ctx.h, 1, 4096, 4096, 4096, 64, 128) == S.SPD_ESTATE

@@ -20,7 +20,7 @@ import numpy as np
 __all__ = [
     "LayerShape", "Workload", "CONFIGS", "get_config", "to_bf16_bits", "bf16_bits_to_f32",
     "normal_bf16", "prefill_inputs", "decode_inputs", "mla_decode_inputs", "mla_prefill_inputs",
-    "mla_weights", "scramble_ops", "trace", "lognormal_lengths", "uniform_lengths",
+    "mla_weights", "scramble_ops", "trace", "lognormal_lengths", "uniform_lengths", "ffn_inputs",
 ]
 
 
@@ -194,6 +194,17 @@ def mla_weights(n_heads: int, nope: int, kv_lora: int, dim_v: int, seed: int):
     w_uk = rng.normal(0.0, MLA_W_STD, size=(n_heads, nope, kv_lora))
     w_uv = rng.normal(0.0, MLA_W_STD, size=(n_heads, kv_lora, dim_v))
     return w_uk, w_uv
+
+
+def ffn_inputs(n_tokens: int, hidden: int, inter: int, seed: int):
+    """Inputs of the gated FFN's first step: activations x [T, hidden] ~ N(0, 1) (a normalised hidden state),
+    weights W_gate, W_up [inter, hidden] ~ N(0, 1 / hidden) (so that the projections are of order one, as after
+    a trained layer's scaling); all rounded once to bf16, returned as uint16 bit patterns."""
+    rng = np.random.default_rng(seed)
+    x = normal_bf16(rng, (n_tokens, hidden))
+    w_gate = normal_bf16(rng, (inter, hidden), std=hidden ** -0.5)
+    w_up = normal_bf16(rng, (inter, hidden), std=hidden ** -0.5)
+    return x, w_gate, w_up
 
 
 # --------------------------------------------------------------------------- allocator op streams
