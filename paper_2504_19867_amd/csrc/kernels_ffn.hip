@@ -7,15 +7,23 @@
 //     y = x . w_gu^T            out[t, 32 b + j] = silu(y[t, 64 b + j]) * y[t, 64 b + 32 + j]
 // silu(z) = z / (1 + exp(-z)).  bf16 in, fp32 accumulation, one rounding to bf16 at the end.
 //
-// A dense contraction: v_mfma_f32_32x32x16_bf16.  One workgroup = 8 waves computes a tile of 256
-// tokens x 256 joint columns (= 128 outputs); the waves form a 2 x 4 grid, each with 128 tokens x 64
-// joint columns: one block of 32 gate columns and the 32 up columns that belong to them, so the
+// A dense contraction: v_mfma_f32_32x32x16_bf16.
+//
+// Prompt batches (ffn_gate_up_kernel): one workgroup = 8 waves computes a tile of 256 tokens x 256
+// joint columns (= 128 outputs); the waves form a 2 x 4 grid, each with 128 tokens x 64 joint
+// columns: one block of 32 gate columns and the 32 up columns that belong to them, so the
 // activation needs nothing but the wave's own accumulators.  Both operands are contiguous along
 // hidden; 32-wide slices of them stream from global memory straight into a ring of four LDS stages
-// (global_load_lds_dwordx4, three slices ahead of the compute, one s_barrier per slice) and are read
-// back with 16-byte reads in operand order.  Rows are 64 bytes in LDS; the four 16-byte chunks of a
-// row are XOR-swizzled with bits 2..3 of the row number, which spreads 16 consecutive rows over all
-// banks.
+// (global_load_lds_dwordx4, one s_barrier per slice) and are read back with 16-byte reads in operand
+// order, one slice ahead of the MFMAs, into a second set of operand registers.  Rows are 64 bytes in
+// LDS; the four 16-byte chunks of a row are XOR-swizzled with bits 2..3 of the row number, which
+// spreads 16 consecutive rows over all banks.
+//
+// Decode batches (ffn_gate_up_small_kernel, up to 256 tokens): the product is bound by reading the
+// weights once, so the work is cut into many small workgroups instead: 64 tokens x 64 joint columns
+// (32 outputs), the four waves taking every fourth 64-wide block of hidden straight from global
+// memory into registers (whole 128-byte lines of every weight row) and adding their partial sums
+// through LDS at the end.
 #include "internal.h"
 
 namespace spd {
@@ -28,12 +36,9 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-constexpr int WAVES = 8;
-constexpr int BM = 256, BNP = 256, BK = 32;     // tokens, joint columns, hidden entries per slice
+constexpr int BK = 32;                          // hidden entries per slice
 constexpr int NSTAGE = 4, PD = NSTAGE - 1;
-constexpr int A_BYTES = BM * BK * 2, B_BYTES = BNP * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
-constexpr int LPW = (A_BYTES + B_BYTES) / 1024 / WAVES;   // 1 KiB load instructions per wave per slice
-static_assert(LPW == 4 && A_BYTES / 1024 == 2 * WAVES, "two A and two B load instructions per wave");
+constexpr int LPW = 4;                          // 1 KiB load instructions per wave per slice: two of x, two of the weights
 
 __device__ inline uint32_t cvt_bf16(float a) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, a}, bf16x2)) & 0xffffu;
@@ -45,50 +50,82 @@ __device__ inline void dma16s(const void* sbase, uint32_t voff, uint32_t lds_byt
 }
 #define SPD_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
 
-__global__ __launch_bounds__(512, 2) void ffn_gate_up_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
-                                                             bf16_t* __restrict__ out, int T, int K, int I, int tiles_m,
-                                                             int tiles_n, int xcds) {
+// MB: 32-token blocks per wave; WNW: waves along the joint columns.  The waves form a 2 x WNW grid,
+// each with 32 MB tokens x 64 joint columns; the workgroup's tile is 64 MB tokens x 64 WNW joint columns.
+// <4, 4>: 256 x 256 for prompt batches; <2, 2>: 128 x 128, four waves, two workgroups per CU, for
+// batches of up to 128 tokens, where the product is bound by reading the weights once and many
+// small workgroups keep more of them in flight.
+template <int MB, int WNW>
+__global__ __launch_bounds__(128 * WNW, 2) void ffn_gate_up_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
+                                                                   bf16_t* __restrict__ out, int T, int K, int I, int tiles_m,
+                                                                   int tiles_n, int xcds) {
+  constexpr int WAVES = 2 * WNW, BM = 64 * MB, BNP = 64 * WNW;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BNP * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+  static_assert((A_BYTES + B_BYTES) / 1024 == LPW * WAVES && A_BYTES / 1024 == 2 * WAVES, "two x and two weight loads per wave");
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n32 = lane & 31, hh = lane >> 5;
-  const int wm = wave >> 2, wn = wave & 3;
-  // Workgroup b runs on XCD b % xcds; every XCD takes a contiguous range of tiles, token tiles
-  // fastest, so that the workgroups running together on an XCD share a slice of the weights.
-  const int total = tiles_m * tiles_n;
-  const int per = (total + xcds - 1) / xcds;
-  const int slot = (int)blockIdx.x / xcds;
-  const int tile_id = ((int)blockIdx.x % xcds) * per + slot;
-  if (slot >= per || tile_id >= total) return;
-  const int tm = tile_id % tiles_m, tn = tile_id / tiles_m;
+  const int wm = wave / WNW, wn = wave % WNW;
+  // Workgroup b runs on XCD b % xcds, and the workgroups of an XCD start in the order of b.  Every
+  // XCD takes a contiguous range of weight tiles (columns) and all token tiles; inside it the tiles
+  // are ordered so that the 16 or so workgroups running together form a block of about 4 x 4 tiles:
+  // each slice of x and of the weights that misses the XCD's L2 then feeds four workgroups.
+  int tm, tn;
+  if (xcds > 1) {
+    const int xcd = (int)blockIdx.x % xcds, slot = (int)blockIdx.x / xcds;
+    const int base = tiles_n / xcds, rem = tiles_n % xcds;
+    const int cnt = base + (xcd < rem ? 1 : 0), start = xcd * base + min(xcd, rem);
+    if (slot >= cnt * tiles_m) return;
+    const int full = cnt / 4;                   // column blocks of four weight tiles; the last one narrower
+    int cb, q, wb;
+    if (slot < full * 4 * tiles_m) {
+      cb = slot / (4 * tiles_m);
+      q = slot % (4 * tiles_m);
+      wb = 4;
+    } else {
+      cb = full;
+      q = slot - full * 4 * tiles_m;
+      wb = cnt - 4 * full;
+    }
+    tm = q / wb;
+    tn = start + 4 * cb + q % wb;
+  } else {
+    if ((int)blockIdx.x >= tiles_m * tiles_n) return;
+    tm = (int)blockIdx.x % tiles_m;
+    tn = (int)blockIdx.x / tiles_m;
+  }
   const int m0 = tm * BM, n0p = tn * BNP;
   const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
   const uint32_t pitch = (uint32_t)K * 2;
 
-  // ---- slice loads.  Load instruction ii = wave + 8 j fills the 64 consecutive 16-byte slots
+  // ---- slice loads.  Load instruction ii = wave + WAVES j fills the 64 consecutive 16-byte slots
   // [64 ii, 64 ii + 64) of the stage: x rows first (row = slot / 4), then weight rows; slot s of a
   // row holds the row's chunk s ^ ((row >> 2) & 3).  Token rows past T re-read row T - 1.
+  constexpr int A_LOADS = A_BYTES / 1024;
   uint32_t ld_voff[LPW];
 #pragma unroll
   for (int j = 0; j < LPW; ++j) {
     const int ii = wave + WAVES * j;
-    const int s = (ii & 15) * 64 + lane, row = s >> 2, chunk = (s & 3) ^ ((row >> 2) & 3);
-    const int grow = ii < 16 ? min(row, T - 1 - m0) : row;
+    const int s = (ii < A_LOADS ? ii : ii - A_LOADS) * 64 + lane, row = s >> 2, chunk = (s & 3) ^ ((row >> 2) & 3);
+    const int grow = ii < A_LOADS ? min(row, T - 1 - m0) : row;
     ld_voff[j] = (uint32_t)grow * pitch + (uint32_t)chunk * 16;
   }
   const char* a_base = (const char*)(x + (size_t)m0 * K);
   const char* b_base = (const char*)(w + (size_t)n0p * K);
   const int n_slices = K / BK;
   int pt = 0, ct = 0;
-  auto produce_one = [&]() __attribute__((always_inline)) {
+  // load instruction j of slice pt; after the last one the slice counts as issued
+  auto produce_piece = [&](int j) __attribute__((always_inline)) {
     if (pt >= n_slices) return;
     const uint32_t stage = __builtin_amdgcn_readfirstlane(smem_base + (uint32_t)(pt % NSTAGE) * STAGE_BYTES);
+    const int ii = wave + WAVES * j;
+    dma16s((ii < A_LOADS ? a_base : b_base) + (size_t)pt * (BK * 2), ld_voff[j], stage + (uint32_t)ii * 1024);
+    if (j == LPW - 1) ++pt;
+  };
+  auto produce_one = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < LPW; ++j) {
-      const int ii = wave + WAVES * j;
-      dma16s((ii < 16 ? a_base : b_base) + (size_t)pt * (BK * 2), ld_voff[j], stage + (uint32_t)ii * 1024);
-    }
-    ++pt;
+    for (int j = 0; j < LPW; ++j) produce_piece(j);
   };
 
   // ---- LDS operand addresses inside a stage: row r, k-step ks (16 hidden entries), lane half hh
@@ -97,15 +134,15 @@ __global__ __launch_bounds__(512, 2) void ffn_gate_up_kernel(const bf16_t* __res
   int a_off[2], b_off[2];
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
-    a_off[ks] = (wm * 128 + n32) * 64 + (((2 * ks + hh) ^ sw) * 16);
+    a_off[ks] = (wm * (32 * MB) + n32) * 64 + (((2 * ks + hh) ^ sw) * 16);
     b_off[ks] = A_BYTES + (wn * 64 + n32) * 64 + (((2 * ks + hh) ^ sw) * 16);
   }
 
   // acc[mb][0] = gate, acc[mb][1] = up: element i of lane (n32, hh) is token 32 mb + 8 (i / 4) + 4 hh + i % 4,
   // column n32 of the wave's block
-  f32x16 acc[4][2];
+  f32x16 acc[MB][2];
 #pragma unroll
-  for (int mb = 0; mb < 4; ++mb)
+  for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
@@ -114,42 +151,72 @@ __global__ __launch_bounds__(512, 2) void ffn_gate_up_kernel(const bf16_t* __res
 #pragma unroll
   for (int t = 0; t < PD; ++t) produce_one();
 
-  for (; ct < n_slices;) {
-    // this wave's loads of slice ct are done when at most (slices issued after it) * LPW remain
-    const int later = pt - ct - 1;
+  // The operands of slice t + 1 are read from LDS into a second set of registers while the matrix
+  // cores work on slice t, so the barrier of a step guards the slice AFTER the one being multiplied.
+  // Reads, tile loads and MFMAs alternate in program order: issued in a bunch behind the barrier, the
+  // reads of all the waves keep the LDS pipe busy for most of a slice's matrix time, and no wave gets
+  // to its MFMAs before its own reads are accepted.
+  constexpr int N_READS = 2 * (MB + 2), N_MEM = N_READS + LPW, N_MFMA = 4 * MB;
+  struct Ops { uint4 a[2][MB], b[2][2]; };
+  auto read_op = [&](int slice, Ops& o, int n) __attribute__((always_inline)) {   // operand n in order of use
+    const char* sbase = smem + (slice % NSTAGE) * STAGE_BYTES;
+    const int ks = n / (MB + 2), r = n % (MB + 2);
+    if (r < 2) o.b[ks][r] = *(const uint4*)(sbase + b_off[ks] + r * (32 * 64));
+    else o.a[ks][r - 2] = *(const uint4*)(sbase + a_off[ks] + (r - 2) * (32 * 64));
+  };
+  auto load_ops = [&](int slice, Ops& o) __attribute__((always_inline)) {
+#pragma unroll
+    for (int n = 0; n < N_READS; ++n) read_op(slice, o, n);
+  };
+  // this wave's loads of slice s are done when at most (slices issued after it) * LPW remain
+  auto wait_slice = [&](int s) __attribute__((always_inline)) {
+    const int later = pt - s - 1;
     if (later >= 2) SPD_WAIT_VMCNT(2 * LPW);
     else if (later == 1) SPD_WAIT_VMCNT(LPW);
     else SPD_WAIT_VMCNT(0);
-    // all waves: the slice has landed, and everyone is done with the one before, whose stage is refilled next
+  };
+  // one step: slice t + 1 becomes readable for all waves (and everyone is done reading slice t - 1,
+  // whose stage is refilled); slice t is multiplied, and the step's memory instructions (the operand
+  // reads of slice t + 1, with the four loads of slice t + 3 evenly among them) go behind its MFMAs
+  auto step = [&](int t, const Ops& cur, Ops& nxt) __attribute__((always_inline)) {
+    const bool more = t + 1 < n_slices;
+    if (more) wait_slice(t + 1);
     asm volatile("s_barrier" ::: "memory");
-    produce_one();
-    const char* sbase = smem + (ct % NSTAGE) * STAGE_BYTES;
-    ++ct;
-    uint4 a[2][4], b[2][2];
+    int n_mem = 0, n_read = 0;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int i = 0; i < N_MFMA; ++i) {
+      const int ks = i / (2 * MB), mb = (i % (2 * MB)) / 2, nb = i % 2;
+      acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cur.a[ks][mb]),
+                                                            __builtin_bit_cast(bf16x8, cur.b[ks][nb]), acc[mb][nb], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) b[ks][nb] = *(const uint4*)(sbase + b_off[ks] + nb * (32 * 64));
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb) a[ks][mb] = *(const uint4*)(sbase + a_off[ks] + mb * (32 * 64));
+      for (; n_mem * N_MFMA < (i + 1) * N_MEM; ++n_mem) {
+        if (n_mem % (N_MEM / LPW) == 1) {
+          produce_piece(n_mem / (N_MEM / LPW));
+        } else {
+          if (more) read_op(t + 1, nxt, n_read);
+          ++n_read;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-          acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[ks][mb]),
-                                                                __builtin_bit_cast(bf16x8, b[ks][nb]), acc[mb][nb], 0, 0, 0);
+  };
+  Ops o0, o1;
+  wait_slice(0);
+  asm volatile("s_barrier" ::: "memory");
+  load_ops(0, o0);
+  for (; ct < n_slices; ct += 2) {
+    step(ct, o0, o1);
+    if (ct + 1 < n_slices) step(ct + 1, o1, o0);
   }
 
   // ---- activation and store: lanes 0..31 of a store hold 32 consecutive outputs of one token
   const int col = tn * (BNP / 2) + wn * 32 + n32;
 #pragma unroll
-  for (int mb = 0; mb < 4; ++mb)
+  for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int t = m0 + wm * 128 + mb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
+      const int t = m0 + wm * (32 * MB) + mb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
       const float g = acc[mb][0][i], u = acc[mb][1][i];
       const float s = g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
       if (t < T) out[(size_t)t * I + col] = (bf16_t)cvt_bf16(s * u);
@@ -169,16 +236,20 @@ __global__ __launch_bounds__(256) void ffn_pack_kernel(const uint4* __restrict__
 
 }  // namespace
 
-int ffn_tile_tokens() { return BM; }
-
-hipError_t launch_ffn_gate_up(const void* x, const void* w_gu, void* out, int T, int K, int I, int xcds, hipStream_t stream) {
+template <int MB, int WNW>
+static hipError_t launch_tiles(const void* x, const void* w_gu, void* out, int T, int K, int I, int xcds, hipStream_t stream) {
+  constexpr int BM = 64 * MB, BNP = 64 * WNW;
   const int tiles_m = (T + BM - 1) / BM, tiles_n = 2 * I / BNP;
-  const int total = tiles_m * tiles_n;
-  if (total < xcds) xcds = 1;
-  const int per = (total + xcds - 1) / xcds;
-  hipLaunchKernelGGL(ffn_gate_up_kernel, dim3((unsigned)(per * xcds)), dim3(64 * WAVES), 0, stream, (const bf16_t*)x,
+  if (tiles_n < xcds) xcds = 1;
+  const int per = xcds > 1 ? ((tiles_n + xcds - 1) / xcds) * tiles_m : tiles_m * tiles_n;
+  hipLaunchKernelGGL((ffn_gate_up_kernel<MB, WNW>), dim3((unsigned)(per * xcds)), dim3(128 * WNW), 0, stream, (const bf16_t*)x,
                      (const bf16_t*)w_gu, (bf16_t*)out, T, K, I, tiles_m, tiles_n, xcds);
   return hipGetLastError();
+}
+
+hipError_t launch_ffn_gate_up(const void* x, const void* w_gu, void* out, int T, int K, int I, int xcds, hipStream_t stream) {
+  if (T <= 128) return launch_tiles<2, 2>(x, w_gu, out, T, K, I, xcds, stream);
+  return launch_tiles<4, 4>(x, w_gu, out, T, K, I, xcds, stream);
 }
 
 hipError_t launch_ffn_pack(const void* w_gate, const void* w_up, void* w_gu, int K, int I, hipStream_t stream) {

@@ -41,7 +41,8 @@ def _run(ctx, phase, xb, wgb, wub, poison_out=True):
     return out[:T], w_gu
 
 
-@pytest.mark.parametrize("T,K,I", [(300, 256, 256), (1, 64, 128), (64, 512, 384), (256, 32, 128), (257, 96, 128), (515, 1024, 512)])
+@pytest.mark.parametrize("T,K,I", [(300, 256, 256), (1, 64, 128), (64, 512, 384), (256, 32, 128), (257, 96, 128), (515, 1024, 512),
+                                   (300, 32, 128), (100, 96, 256), (200, 320, 128), (130, 4096, 128)])
 def test_gate_up_matches_oracle(T, K, I):
     ctx = S.Context(0)
     xb, wgb, wub = W.ffn_inputs(T, K, I, seed=100 + T)
