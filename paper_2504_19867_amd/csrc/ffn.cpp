@@ -1,4 +1,5 @@
 // Entry points of the gated FFN's first step (gate and up projection as one GEMM).
+#include <algorithm>
 #include <cstdint>
 
 #include "internal.h"
@@ -37,6 +38,6 @@ extern "C" int spd_ffn_gate_up(spd_ctx* ctx, int phase, const void* x, const voi
   hipStream_t stream;
   if ((rc = phase_enter(ctx, phase, &stream)) != SPD_OK) return rc;
   if ((rc = kernel_timing_mark(ctx, phase, 0, stream)) != SPD_OK) return rc;
-  SPD_HIP(launch_ffn_gate_up(x, w_gu, out, n_tokens, hidden, inter, ctx->xcds, stream));
+  SPD_HIP(launch_ffn_gate_up(x, w_gu, out, n_tokens, hidden, inter, ctx->xcds, std::max(1, ctx->phase[phase].active_cus), stream));
   return kernel_timing_mark(ctx, phase, 1, stream);
 }

@@ -172,7 +172,8 @@ hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out
                           hipStream_t stream);
 // x [T, K], w_gu [2 I, K] (joint gate/up rows in blocks of 32 + 32), out [T, I], all bf16 in device memory;
 // K a multiple of 32, I a multiple of 128
-hipError_t launch_ffn_gate_up(const void* x, const void* w_gu, void* out, int T, int K, int I, int xcds, hipStream_t stream);
+hipError_t launch_ffn_gate_up(const void* x, const void* w_gu, void* out, int T, int K, int I, int xcds, int cus,
+                              hipStream_t stream);
 hipError_t launch_ffn_pack(const void* w_gate, const void* w_up, void* w_gu, int K, int I, hipStream_t stream);
 // d_pos, d_w may be device-readable pinned host memory
 hipError_t launch_rope(void* q, int n_q_heads, void* k, int n_kv_heads, int dim, int rot, int off, bool interleaved,

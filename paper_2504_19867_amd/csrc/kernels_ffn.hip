@@ -247,8 +247,12 @@ static hipError_t launch_tiles(const void* x, const void* w_gu, void* out, int T
   return hipGetLastError();
 }
 
-hipError_t launch_ffn_gate_up(const void* x, const void* w_gu, void* out, int T, int K, int I, int xcds, hipStream_t stream) {
-  if (T <= 128) return launch_tiles<2, 2>(x, w_gu, out, T, K, I, xcds, stream);
+hipError_t launch_ffn_gate_up(const void* x, const void* w_gu, void* out, int T, int K, int I, int xcds, int cus,
+                              hipStream_t stream) {
+  // small batches are bound by reading the weights: the small tile where the large one would leave
+  // half of the share's compute units without a workgroup
+  const int large_tiles = ((T + 255) / 256) * (2 * I / 256);
+  if (T <= 128 || (T <= 256 && 2 * large_tiles <= cus)) return launch_tiles<2, 2>(x, w_gu, out, T, K, I, xcds, stream);
   return launch_tiles<4, 4>(x, w_gu, out, T, K, I, xcds, stream);
 }
 
