@@ -102,6 +102,87 @@ __global__ __launch_bounds__(256) void kv_write_kernel(char* __restrict__ base, 
   }
 }
 
+// The same page write for GQA pools with dk, dv <= 128, one workgroup per 16-token tile and group of
+// up to HG KV heads: the descriptor (possibly in pinned host memory) is fetched once per group
+// instead of once per head, and the row reads of all the group's heads are in flight together
+// before the first head goes through LDS.  grid (n_tiles + copy_cols, ceil(Hkv / HG)), block 256.
+template <int HG>
+__global__ __launch_bounds__(256) void kv_write_heads_kernel(char* __restrict__ base, uint64_t page_bytes, uint32_t head_bytes,
+                                                             uint32_t tile_bytes, uint32_t tile_k_bytes,
+                                                             const TileDesc* __restrict__ descs, const bf16_t* __restrict__ k,
+                                                             const bf16_t* __restrict__ v, int Hkv, int dk, int dv, int n_tiles,
+                                                             uint4* __restrict__ copy_dst, const uint4* __restrict__ copy_src,
+                                                             uint64_t copy_n16) {
+  if ((int)blockIdx.x >= n_tiles) {
+    const uint64_t blk = (uint64_t)(blockIdx.x - n_tiles) * gridDim.y + blockIdx.y;
+    const uint64_t stride = (uint64_t)(gridDim.x - n_tiles) * gridDim.y * blockDim.x;
+    for (uint64_t i = blk * blockDim.x + threadIdx.x; i < copy_n16; i += stride) copy_dst[i] = copy_src[i];
+    return;
+  }
+  __shared__ uint4 ks[TILE_T][16 + 1];              // dk <= 128: 16 pieces per token, one of padding
+  __shared__ bf16_t vs[TILE_T][128 + 8];            // dv <= 128; 8 elements of padding per row
+  const TileDesc d = descs[blockIdx.x];
+  const int g0 = blockIdx.y * HG, ng = min(HG, Hkv - g0);
+  const int i = threadIdx.x;
+  const int ck_n = dk >> 3, cv_n = dv >> 3;         // 16-byte pieces per K row, per V row
+  const int tk = i / ck_n, ck = i % ck_n, tv = i / cv_n, cv = i % cv_n;
+  const bool k_ok = i < ck_n * TILE_T && tk >= d.t_begin && tk < d.t_end;
+  const bool v_ok = i < cv_n * TILE_T && tv >= d.t_begin && tv < d.t_end;
+  uint4 kr[HG], vr[HG];
+#pragma unroll
+  for (int g = 0; g < HG; ++g) {
+    kr[g] = vr[g] = uint4{0, 0, 0, 0};
+    if (g < ng && k_ok) kr[g] = *(const uint4*)(k + ((size_t)(d.src_row + tk - d.t_begin) * Hkv + g0 + g) * dk + ck * 8);
+    if (g < ng && v_ok) vr[g] = *(const uint4*)(v + ((size_t)(d.src_row + tv - d.t_begin) * Hkv + g0 + g) * dv + cv * 8);
+  }
+  const int v_items = (dv >> 5) * 64;
+#pragma unroll
+  for (int g = 0; g < HG; ++g) {
+    if (g >= ng) break;
+    char* tile = base + (uint64_t)d.page * page_bytes + (uint64_t)(g0 + g) * head_bytes + (uint64_t)d.sub * tile_bytes;
+    if (k_ok) ks[tk][ck] = kr[g];
+    if (v_ok) *(uint4*)&vs[tv][cv * 8] = vr[g];
+    __syncthreads();
+    // K part [chunk][token][8 dims]
+    if (i < ck_n * TILE_T) {
+      const int t = i & 15, c = i >> 4;
+      if (t >= d.t_begin && t < d.t_end) *(uint4*)(tile + ((size_t)(c * 16 + t) << 4)) = ks[t][c];
+    }
+    // V part [d/32][token quad][d%16][(d/16)%2][4 tokens]
+    if (i < v_items) {
+      bf16_t* vt = (bf16_t*)(tile + tile_k_bytes);
+      const int m = i & 15, c4 = (i >> 4) & 3, blk2 = i >> 6;
+      bf16_t vals[8];
+      bool all = true;
+#pragma unroll
+      for (int par = 0; par < 2; ++par)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+          const int t = 4 * c4 + tt, dd = 32 * blk2 + 16 * par + m;
+          const bool ok = t >= d.t_begin && t < d.t_end;
+          all = all && ok;
+          vals[par * 4 + tt] = ok ? vs[t][dd] : (bf16_t)0;
+        }
+      bf16_t* dst = vt + ((size_t)((blk2 * 4 + c4) * 16 + m) << 3);
+      if (all) {
+        uint4 pk;
+        pk.x = vals[0] | ((uint32_t)vals[1] << 16);
+        pk.y = vals[2] | ((uint32_t)vals[3] << 16);
+        pk.z = vals[4] | ((uint32_t)vals[5] << 16);
+        pk.w = vals[6] | ((uint32_t)vals[7] << 16);
+        *(uint4*)dst = pk;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int t = 4 * c4 + (e & 3);
+          if (t >= d.t_begin && t < d.t_end) dst[e] = vals[e];
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
 // Inverse of kv_write_kernel, with the same 16-byte pieces: K pieces go straight back to their rows,
 // the V tile is un-transposed through LDS and leaves as 16-byte row pieces.
 __global__ __launch_bounds__(256) void kv_gather_kernel(const char* __restrict__ base, uint64_t page_bytes,
@@ -174,6 +255,16 @@ hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d
   const uint64_t n16 = copy_dst ? (copy_bytes + 15) / 16 : 0;
   const int copy_cols = n16 ? (int)std::min<uint64_t>(16, (n16 + 256ull * g.Hkv - 1) / (256ull * g.Hkv)) : 0;
   if (n_tiles <= 0 && copy_cols == 0) return hipSuccess;
+  if (g.kind == SPD_KV_GQA && v != nullptr && g.dk <= 128 && g.dv <= 128 && g.Hkv >= 2) {
+    constexpr int HG = 8;
+    const int groups = (g.Hkv + HG - 1) / HG;
+    // the metadata copy keeps its share of workgroups: copy_cols x Hkv of them before, the same number now
+    const int cols = copy_cols ? (copy_cols * g.Hkv + groups - 1) / groups : 0;
+    hipLaunchKernelGGL(kv_write_heads_kernel<HG>, dim3(n_tiles + cols, groups), dim3(256), 0, stream, pool_base, g.page_bytes,
+                       g.head_bytes, g.tile_bytes, g.tile_k_bytes, d_tiles, (const bf16_t*)k, (const bf16_t*)v, g.Hkv, g.dk,
+                       g.dv, n_tiles, (uint4*)copy_dst, (const uint4*)copy_src, n16);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(kv_write_kernel, dim3(n_tiles + copy_cols, g.Hkv), dim3(256), 0, stream, pool_base, g.page_bytes,
                      g.head_bytes, g.tile_bytes, g.tile_k_bytes, d_tiles, (const bf16_t*)k, (const bf16_t*)v, g.Hkv, g.dk,
                      g.dv, g.kind == SPD_KV_MLA_LATENT ? 1 : 0, n_tiles, (uint4*)copy_dst, (const uint4*)copy_src, n16);
