@@ -3,6 +3,9 @@
 kernel time by HIP events on the prefill partition for a prompt batch (matrix-core bound: 4 T hidden inter flops)
 and on the decode partition for a decode batch (bound by reading the weights once: 4 hidden inter bytes).
 Inputs are normally distributed (constant operands would let the matrix cores clock higher).
+Then both at once on the two halves of the chip: prompt-batch GEMMs on the prefill partition while the decode
+partition runs decode-batch GEMMs back to back (the paper's point: a compute-bound and a bandwidth-bound phase
+share one GPU).
 Run as `python -m paper_2504_19867_amd.ffn_bench` (`--quick`: the Llama-3-8B prompt batch on half the chip only,
 three launches, for counter runs)."""
 import os
@@ -51,7 +54,48 @@ def main():
                 share = cus / total
                 print(f"{model:18s} {name:22s} on {cus:3d} CUs: {med * 1e3:8.1f} us  {tf:7.1f} TFLOP/s ({100 * tf / (PEAK_TFLOPS * share):4.1f} % of the "
                       f"share's MFMA peak)  {gbs:6.0f} GB/s ({100 * gbs / PEAK_GBS:4.1f} % of HBM)", flush=True)
+    if not quick:
+        concurrent(ctx, dev, total)
     ctx.close()
+
+
+def concurrent(ctx, dev, total):
+    """Llama-3-8B shape: 8 prompt-batch GEMMs on the prefill half, decode-batch GEMMs on the other half meanwhile."""
+    model, K, I = SHAPES[0]
+    ctx.set_partition(total // 2, total // 2)
+    wg = torch.randn((I, K), device=dev, dtype=torch.float32).mul_(K ** -0.5).to(torch.bfloat16)
+    wu = torch.randn((I, K), device=dev, dtype=torch.float32).mul_(K ** -0.5).to(torch.bfloat16)
+    w_gu = torch.empty((2 * I, K), device=dev, dtype=torch.bfloat16)
+    ctx.ffn_pack_gate_up(PRE, wg, wu, w_gu, K, I)
+    xp = torch.randn((8192, K), device=dev, dtype=torch.bfloat16)
+    op = torch.empty((8192, I), device=dev, dtype=torch.bfloat16)
+    xd = torch.randn((64, K), device=dev, dtype=torch.bfloat16)
+    od = torch.empty((64, I), device=dev, dtype=torch.bfloat16)
+    res = {}
+    for mode in ("solo", "concurrent"):
+        for _ in range(2):
+            ctx.ffn_gate_up(PRE, xp, w_gu, op, 8192, K, I)
+            ctx.ffn_gate_up(DEC, xd, w_gu, od, 64, K, I)
+        ctx.phase_sync(PRE); ctx.phase_sync(DEC)
+        ctx.phase_kernel_ms(PRE); ctx.phase_kernel_ms(DEC)
+        if mode == "solo":
+            for _ in range(8):
+                ctx.ffn_gate_up(PRE, xp, w_gu, op, 8192, K, I)
+            ctx.phase_sync(PRE)
+            for _ in range(200):
+                ctx.ffn_gate_up(DEC, xd, w_gu, od, 64, K, I)
+            ctx.phase_sync(DEC)
+        else:
+            for _ in range(8):                   # about 35 decode GEMMs fit beside one prompt-batch GEMM
+                ctx.ffn_gate_up(PRE, xp, w_gu, op, 8192, K, I)
+                for _ in range(30):
+                    ctx.ffn_gate_up(DEC, xd, w_gu, od, 64, K, I)
+            ctx.phase_sync(PRE); ctx.phase_sync(DEC)
+        pk, dk = sorted(ctx.phase_kernel_ms(PRE)), sorted(ctx.phase_kernel_ms(DEC))
+        res[mode] = (pk[len(pk) // 2], dk[len(dk) // 2])
+    for mode, (p, d) in res.items():
+        print(f"{model} on {total // 2} + {total // 2} CUs, {mode:10s}: prompt-batch GEMM {p * 1e3:7.1f} us ({4.0 * 8192 * K * I / p / 1e9:6.1f} TFLOP/s)   "
+              f"decode-batch GEMM {d * 1e3:6.1f} us ({4.0 * K * I / d / 1e6:5.0f} GB/s of weights)", flush=True)
 
 
 if __name__ == "__main__":
