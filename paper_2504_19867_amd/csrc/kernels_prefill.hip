@@ -26,8 +26,8 @@
 // which a fresh workgroup would have to wait for, arrive while the item before is still computing.
 //
 // K and V tiles of 64 keys stream from global memory straight into a ring of LDS stages with
-// global_load_lds_dwordx4 (no register staging, no LDS stores), PD tiles ahead of the compute;
-// one s_barrier per tile.  K rows are read back with 16-byte reads in A-operand order; V stays
+// global_load_lds_dwordx4 (no register staging, no LDS stores), ahead of the compute; one
+// s_barrier per pair of tiles where the ring has four stages (one per tile with three).  K rows are read back with 16-byte reads in A-operand order; V stays
 // in its natural [key][dim] order and the transposition that the second product needs is done
 // by the LDS transpose read ds_read_b64_tr_b16.  Both tiles are XOR-swizzled at 16-byte
 // granularity against bank conflicts.
@@ -190,6 +190,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
   // The tile loop is unrolled over the ring's stages so that the stage offset is part of each LDS
   // read's 16-bit immediate; stages 2 and 3 lie beyond its reach and get a second set of lane addresses.
   constexpr bool UNROLL = NSTAGE == 4 && 2 * STAGE_BYTES <= 65536;
+  constexpr bool PAIRS = UNROLL;                // a ring of four holds the pair in use and the pair in flight
   int k_off2[KS], v_off2[VB];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
 
   int ct = 0;                                   // tiles consumed so far (tile number ct sits in stage ct % NSTAGE)
 #pragma unroll
-  for (int t = 0; t < PD; ++t) produce_one();
+  for (int t = 0; t < (PAIRS ? 2 : PD); ++t) produce_one();
 
   // ---- state of the item being computed
   PrefillWork w;
@@ -273,15 +274,28 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
   auto tile = [&](auto stc) {
     const int ST = stc;                         // ring stage of tile kt: a constant when the loop is unrolled
     const int kv0 = kt * BN;
-    // this wave's loads of tile kt are done when at most (tiles issued after kt) * LPW remain
-    // this wave's loads of the tile are done when at most (tiles issued after it) * LPW remain
-    const int later = pt - ct - 1;
-    if (later >= 2) SPD_WAIT_VMCNT(2 * LPW);
-    else if (later == 1) SPD_WAIT_VMCNT(LPW);
-    else SPD_WAIT_VMCNT(0);
-    // all waves: the tile has landed, and everyone is done with the one before, whose stage is refilled next
-    asm volatile("s_barrier" ::: "memory");
-    produce_one();
+    if constexpr (PAIRS) {
+      // Tiles go in pairs: one wait and one barrier for two tiles, after which the waves run free
+      // for two tiles' worth of work (the two waves of a SIMD drift apart, and one's matrix work
+      // falls beside the other's softmax).  At the barrier the pair has landed and everyone is done
+      // with the pair before, whose two stages are refilled, one now and one a tile later.
+      if ((ST & 1) == 0) {
+        SPD_WAIT_VMCNT(0);
+        asm volatile("s_barrier" ::: "memory");
+        produce_one();
+      } else {
+        produce_one();                          // the pair's second tile a tile later: eight loads at once queue up
+      }
+    } else {
+      // this wave's loads of the tile are done when at most (tiles issued after it) * LPW remain
+      const int later = pt - ct - 1;
+      if (later >= 2) SPD_WAIT_VMCNT(2 * LPW);
+      else if (later == 1) SPD_WAIT_VMCNT(LPW);
+      else SPD_WAIT_VMCNT(0);
+      // all waves: the tile has landed, and everyone is done with the one before, whose stage is refilled next
+      asm volatile("s_barrier" ::: "memory");
+      produce_one();
+    }
     ++ct;
     if (!wave_active || kv0 > pos0 + 31) return;               // every key of the tile is in this wave's future
 
