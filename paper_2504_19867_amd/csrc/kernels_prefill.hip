@@ -342,45 +342,59 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
         for (int i = 0; i < 16; ++i)
           if (kv0 + 32 * b + 8 * (i >> 2) + 4 * hh + (i & 3) > pos) S[b][i] = -INFINITY;
     }
-    float mx = S[0][0];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[0][i]);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[1][i]);
-    {
-      // the other half of the wave holds the other 32 keys of the same query: exchange on the
-      // vector ALU (swap of the upper half of one register with the lower half of another;
-      // written as machine code: the compiler's builtin for it loses the second result)
-      float mx2 = mx;
-      asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(mx), "+v"(mx2));
-      mx = fmaxf(mx, mx2);
-    }
-    const float m_new = fmaxf(m, mx);
-    const float mc = m_new * c;
+    // p = exp2(S c - m c) against a reference m per query that need not be the running maximum: any
+    // reference gives the same softmax as long as nothing overflows, and bf16 and fp32 keep their
+    // relative precision over the whole exponent range.  So the tile's maximum is not computed at
+    // all unless the row sum says that the reference is out of range (an item's first tile, where
+    // m = -inf makes every p infinite or NaN, or a tile whose scores exceed the reference by 2^60):
+    // then the reference moves to the true maximum, the accumulators are rescaled, and p is redone.
     uint32_t pb[2][8];
-    float ls[4] = {0.f, 0.f, 0.f, 0.f};
+    auto softmax_p = [&](float mc) -> float {
+      float ls[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int i = 0; i < 16; i += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(S[b][i] * c - mc);
-        const float p1 = __builtin_amdgcn_exp2f(S[b][i + 1] * c - mc);
-        pb[b][i >> 1] = cvt_pk_bf16(p0, p1);
-        // the row sum runs over the rounded values, the ones the second product multiplies: two per
-        // instruction (the compiler places the wait states that a dot product's result needs)
-        ls[(i >> 1) & 3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pb[b][i >> 1]),
-                                                           __builtin_bit_cast(bf16x2, ones2), ls[(i >> 1) & 3], false);
+        for (int i = 0; i < 16; i += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(S[b][i] * c - mc);
+          const float p1 = __builtin_amdgcn_exp2f(S[b][i + 1] * c - mc);
+          pb[b][i >> 1] = cvt_pk_bf16(p0, p1);
+          // the row sum runs over the rounded values, the ones the second product multiplies: two per
+          // instruction (the compiler places the wait states that a dot product's result needs)
+          ls[(i >> 1) & 3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pb[b][i >> 1]),
+                                                             __builtin_bit_cast(bf16x2, ones2), ls[(i >> 1) & 3], false);
+        }
+      return (ls[0] + ls[1]) + (ls[2] + ls[3]);
+    };
+    // (the 192-dim variant has no registers to keep S alive for a second pass: it takes the maximum first, every tile)
+    constexpr bool LAZY = DQK <= 128;
+    float psum = 0.f;
+    if constexpr (LAZY) psum = softmax_p(m * c);
+    if (!LAZY || __builtin_amdgcn_ballot_w64(!(psum < 0x1p60f)) != 0) {
+      float mx = S[0][0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[0][i]);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[1][i]);
+      {
+        // the other half of the wave holds the other 32 keys of the same query: exchange on the
+        // vector ALU (swap of the upper half of one register with the lower half of another;
+        // written as machine code: the compiler's builtin for it loses the second result)
+        float mx2 = mx;
+        asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(mx), "+v"(mx2));
+        mx = fmaxf(mx, mx2);
       }
-    const float psum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
-    // the running maximum rarely moves after the first tiles: rescale only when some lane needs it
-    if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
-      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
-      l *= alpha;
+      const float m_new = fmaxf(m, mx);
+      // (the eager variant: the running maximum rarely moves after the first tiles, rescale only when some lane needs it)
+      if (LAZY || __builtin_amdgcn_ballot_w64(m_new > m) != 0) {
+        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+        l *= alpha;
 #pragma unroll
-      for (int blk = 0; blk < VB; ++blk)
+        for (int blk = 0; blk < VB; ++blk)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) O[blk][e] *= alpha;
-      m = m_new;
+          for (int e = 0; e < 16; ++e) O[blk][e] *= alpha;
+        m = m_new;
+      }
+      psum = softmax_p(m * c);
     }
     l += psum;
 

@@ -197,6 +197,25 @@ def test_prefill_ragged_lengths(H, Hkv, d):
     gp.close()
 
 
+@pytest.mark.parametrize("rise", [30.0, 100.0, 400.0, -200.0])
+@pytest.mark.parametrize("H,Hkv,d", [(8, 2, 128), (4, 4, 64)])
+def test_prefill_scores_drifting_along_the_keys(H, Hkv, d, rise):
+    """Scores that climb (or fall) steadily from the first key to the last: the softmax reference of a row has to
+    follow them over many powers of two inside one prompt (the kernel moves it only when it must), or must stay
+    where the first keys put it."""
+    layer = W.LayerShape("gqa", H, Hkv, d, d, 16)
+    lens = (700, 64, 1, 333)
+    scale = 1.0 / math.sqrt(d)
+    q, k, v, cu = W.prefill_inputs_drifting(layer, lens, seed=int(abs(rise)) + d, rise=rise, scale=scale)
+    gp = GpuPool(layer, 128, poison=True)
+    out = torch.empty((q.shape[0], H, d), dtype=torch.bfloat16, device=DEV)
+    gp.pool.prefill_step([1, 2, 3, 4], cu, dev_bf16(q), dev_bf16(k), dev_bf16(v), out, H, Hkv, d, d, scale)
+    gp.ctx.phase_sync(PRE)
+    want = OA.prefill_attention(f64(q), f64(k), f64(v), cu, scale)
+    assert_parity(host_f64(out), want, f"prefill drifting scores rise={rise}")
+    gp.close()
+
+
 @pytest.mark.parametrize("H,Hkv,d", [(16, 2, 128), (8, 1, 64), (32, 2, 128), (6, 2, 128), (12, 2, 64), (5, 1, 128)])
 def test_prefill_head_groupings(H, Hkv, d):
     """Every way the 8 waves of a workgroup are split over query heads and row sub-tiles: group sizes

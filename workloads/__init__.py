@@ -20,7 +20,7 @@ import numpy as np
 __all__ = [
     "LayerShape", "Workload", "CONFIGS", "get_config", "to_bf16_bits", "bf16_bits_to_f32",
     "normal_bf16", "prefill_inputs", "decode_inputs", "mla_decode_inputs", "mla_prefill_inputs",
-    "mla_weights", "scramble_ops", "trace", "lognormal_lengths", "uniform_lengths", "ffn_inputs",
+    "mla_weights", "scramble_ops", "trace", "lognormal_lengths", "uniform_lengths", "ffn_inputs", "prefill_inputs_drifting",
 ]
 
 
@@ -134,6 +134,20 @@ def prefill_inputs(layer: LayerShape, lens, seed: int):
     cu = np.zeros(len(lens) + 1, dtype=np.int32)
     cu[1:] = np.cumsum(lens)
     return q, k, v, cu
+
+
+def prefill_inputs_drifting(layer: LayerShape, lens, seed: int, rise: float, scale: float):
+    """prefill_inputs with scores that drift along the keys: entry 0 of every query is 8 and entry 0 of the key at
+    position j of a prompt of length L is (j / L) * rise / (8 * scale), so scale * q.k gains `rise` (natural-log
+    units; negative: loses) from the first key to the last, on top of the random part.  For softmax paths whose
+    reference maximum has to move (or must not) inside a prompt."""
+    q, k, v, cu = prefill_inputs(layer, lens, seed)
+    qf, kf = bf16_bits_to_f32(q), bf16_bits_to_f32(k)
+    qf[:, :, 0] = 8.0
+    for a, b in zip(cu[:-1], cu[1:]):
+        L = int(b - a)
+        kf[a:b, :, 0] = (np.arange(L, dtype=np.float32) / L * np.float32(rise / (8.0 * scale)))[:, None]
+    return to_bf16_bits(qf), to_bf16_bits(kf), v, cu
 
 
 def decode_inputs(layer: LayerShape, ctx_lens, seed: int):
