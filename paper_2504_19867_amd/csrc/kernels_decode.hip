@@ -41,6 +41,15 @@ struct TileFrag {          // two 16-token tiles, K and V parts, in operand orde
   uint4 v[2][D / 32];
 };
 
+// A 16-byte load of data that is read exactly once (KV pages in a decode step): marked non-temporal,
+// so that the stream does not push the prefill partition's K/V tiles, which ARE re-read, out of the L2
+// the two partitions share.
+__device__ inline uint4 load_once(const uint4* p) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 r = __builtin_nontemporal_load((const u32x4*)p);
+  return uint4{r.x, r.y, r.z, r.w};
+}
+
 template <int D>
 __device__ inline void load_step(TileFrag<D>& f, const char* __restrict__ pool, uint64_t page_bytes,
                                  uint32_t tile_bytes, int tiles_per_page, const int32_t* __restrict__ bt_row,
@@ -54,9 +63,9 @@ __device__ inline void load_step(TileFrag<D>& f, const char* __restrict__ pool, 
     const uint4* kp = (const uint4*)p + lane;
     const uint4* vp = (const uint4*)(p + TILE_T * D * 2) + lane;
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) f.k[u][s] = kp[s * 64];
+    for (int s = 0; s < D / 32; ++s) f.k[u][s] = load_once(kp + s * 64);
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) f.v[u][s] = vp[s * 64];
+    for (int s = 0; s < D / 32; ++s) f.v[u][s] = load_once(vp + s * 64);
   }
 }
 

@@ -60,7 +60,8 @@ __device__ inline void mla_dma16(const void* gptr, uint32_t lds_byte_addr) {
 }
 // The same with the address split in a wave-uniform base and a 32-bit per-lane offset.
 __device__ inline void mla_dma16s(const void* sbase, uint32_t voff, uint32_t lds_byte_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase) : "memory");
+  // non-temporal: a decode step reads every latent row once, and the L2 is shared with the prefill partition
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase) : "memory");
 }
 // max over the four 16-lane rows of a wave, on the vector ALU: the row swaps exchange odd rows of
 // the first register with even rows of the second (rows of 16, then of 32 lanes)

@@ -12,6 +12,15 @@ namespace spd {
 
 typedef unsigned short bf16_t;
 
+// 16-byte accesses of data that passes through once (rows on their way into pages, pages on their
+// way out): marked non-temporal, so that these streams leave the L2's contents to the attention kernels.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline uint4 load_once(const void* p) {
+  const u32x4 r = __builtin_nontemporal_load((const u32x4*)p);
+  return uint4{r.x, r.y, r.z, r.w};
+}
+__device__ inline void store_once(void* p, uint4 v) { __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, (u32x4*)p); }
+
 // grid (n_tiles + copy_cols, n_kv_heads), block 256.  One workgroup copies the touched token slots
 // of one 16-token tile of one KV head.  The descriptors may lie in pinned host memory (one read
 // per workgroup).  Workgroups past n_tiles copy copy_n16 16-byte pieces copy_src -> copy_dst
@@ -132,8 +141,8 @@ __global__ __launch_bounds__(256) void kv_write_heads_kernel(char* __restrict__ 
 #pragma unroll
   for (int g = 0; g < HG; ++g) {
     kr[g] = vr[g] = uint4{0, 0, 0, 0};
-    if (g < ng && k_ok) kr[g] = *(const uint4*)(k + ((size_t)(d.src_row + tk - d.t_begin) * Hkv + g0 + g) * dk + ck * 8);
-    if (g < ng && v_ok) vr[g] = *(const uint4*)(v + ((size_t)(d.src_row + tv - d.t_begin) * Hkv + g0 + g) * dv + cv * 8);
+    if (g < ng && k_ok) kr[g] = load_once(k + ((size_t)(d.src_row + tk - d.t_begin) * Hkv + g0 + g) * dk + ck * 8);
+    if (g < ng && v_ok) vr[g] = load_once(v + ((size_t)(d.src_row + tv - d.t_begin) * Hkv + g0 + g) * dv + cv * 8);
   }
   const int v_items = (dv >> 5) * 64;
 #pragma unroll
@@ -146,7 +155,7 @@ __global__ __launch_bounds__(256) void kv_write_heads_kernel(char* __restrict__ 
     // K part [chunk][token][8 dims]
     if (i < ck_n * TILE_T) {
       const int t = i & 15, c = i >> 4;
-      if (t >= d.t_begin && t < d.t_end) *(uint4*)(tile + ((size_t)(c * 16 + t) << 4)) = ks[t][c];
+      if (t >= d.t_begin && t < d.t_end) store_once(tile + ((size_t)(c * 16 + t) << 4), ks[t][c]);
     }
     // V part [d/32][token quad][d%16][(d/16)%2][4 tokens]
     if (i < v_items) {
@@ -170,7 +179,7 @@ __global__ __launch_bounds__(256) void kv_write_heads_kernel(char* __restrict__ 
         pk.y = vals[2] | ((uint32_t)vals[3] << 16);
         pk.z = vals[4] | ((uint32_t)vals[5] << 16);
         pk.w = vals[6] | ((uint32_t)vals[7] << 16);
-        *(uint4*)dst = pk;
+        store_once(dst, pk);
       } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
