@@ -244,20 +244,27 @@ int spd_rope_qk(spd_ctx* ctx, int phase, const spd_rope_config* cfg, const int32
  * two GEMMs of the gated FFN are fused into one).  The paper gives no formula; this is the
  * published gated (SwiGLU) FFN of the Llama models:
  *     g = x W_gate^T,  u = x W_up^T,  out = silu(g) * u,  silu(z) = z / (1 + exp(-z))
- * computed as ONE product of x with the joint matrix w_gu [2 inter, hidden], whose rows
+ * computed as ONE product of x with the joint matrix [2 inter, hidden], whose rows
  * 64 b .. 64 b + 31 are rows 32 b .. 32 b + 31 of W_gate and rows 64 b + 32 .. 64 b + 63 the rows
  * with the same numbers of W_up (so that a gate column and its up column meet in one wave), with the
  * activation applied to the fp32 accumulators and one rounding to bf16 (nearest even) at the end.
- * x device [n_tokens, hidden], w_gu device [2 inter, hidden], out device [n_tokens, inter], bf16,
- * row-major; x and w_gu 16-byte aligned; hidden a multiple of 32, inter a multiple of 128;
- * n_tokens >= 0 (0: nothing is enqueued).  Enqueued on `phase`'s current stream, i.e. on that
- * phase's compute units; the buffers belong to the caller and must stay valid until the stream
- * has run the call.  SPD_EINVAL on any violated condition, nothing enqueued. */
+ * w_gu holds the joint matrix in PACKED form (spd_ffn_pack_gate_up writes it): tiles of 256 joint
+ * rows x 32 hidden entries (16 KiB), tile (tn, ks) at byte ((tn * hidden / 32) + ks) * 16384; inside
+ * a tile joint row 256 tn + r keeps 64 bytes at r * 64, and its 16-byte piece number s (0..3)
+ * holds the hidden entries 32 ks + 8 (s ^ ((r >> 2) & 3)) .. + 7.  (The order of a tile in the
+ * kernel's LDS stage: a weight load is 1 KiB of consecutive bytes, and a batch of a few tokens,
+ * which is bound by reading the weights once, streams them.)
+ * x device [n_tokens, hidden] row-major, w_gu device 2 * inter * hidden elements as above, out device
+ * [n_tokens, inter] row-major, bf16; x and w_gu 16-byte aligned; hidden a multiple of 32, inter a
+ * multiple of 128; n_tokens >= 0 (0: nothing is enqueued).  Enqueued on `phase`'s current stream,
+ * i.e. on that phase's compute units; the buffers belong to the caller and must stay valid until the
+ * stream has run the call.  SPD_EINVAL on any violated condition, nothing enqueued. */
 int spd_ffn_gate_up(spd_ctx* ctx, int phase, const void* x, const void* w_gu, void* out, int32_t n_tokens,
                     int32_t hidden, int32_t inter);
-/* Builds the joint matrix w_gu device [2 inter, hidden] from w_gate, w_up device [inter, hidden]
- * (bf16, 16-byte aligned, same conditions on hidden and inter; a copy, done once per layer at load
- * time).  Enqueued on `phase`'s current stream. */
+/* Writes the packed joint matrix w_gu (device, 2 * inter * hidden elements, layout above) from
+ * w_gate, w_up device [inter, hidden] row-major (bf16, 16-byte aligned, same conditions on hidden
+ * and inter; a permutation of 16-byte pieces, done once per layer at load time).  Enqueued on
+ * `phase`'s current stream. */
 int spd_ffn_pack_gate_up(spd_ctx* ctx, int phase, const void* w_gate, const void* w_up, void* w_gu, int32_t hidden,
                          int32_t inter);
 

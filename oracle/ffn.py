@@ -41,7 +41,7 @@ def gate_up(x: np.ndarray, w_gate: np.ndarray, w_up: np.ndarray) -> np.ndarray:
     return silu(g) * u
 
 
-def pack_gate_up(w_gate: np.ndarray, w_up: np.ndarray) -> np.ndarray:
+def joint_rows(w_gate: np.ndarray, w_up: np.ndarray) -> np.ndarray:
     """The joint [2 inter, hidden] matrix: rows 64 b .. 64 b + 31 are gate rows 32 b .. 32 b + 31, rows
     64 b + 32 .. 64 b + 63 the up rows with the same numbers.  inter must be a multiple of 32."""
     w_gate = np.asarray(w_gate)
@@ -56,16 +56,59 @@ def pack_gate_up(w_gate: np.ndarray, w_up: np.ndarray) -> np.ndarray:
     return out
 
 
-def gate_up_packed(x: np.ndarray, w_gu: np.ndarray) -> np.ndarray:
-    """The same result from the joint matrix: ONE product y = x W_gu^T, then out column 32 b + j is
+def gate_up_joint(x: np.ndarray, w_joint: np.ndarray) -> np.ndarray:
+    """The same result from the joint matrix: ONE product y = x W_joint^T, then out column 32 b + j is
     silu(y[:, 64 b + j]) * y[:, 64 b + 32 + j]."""
     x = np.asarray(x, dtype=np.float64)
-    w_gu = np.asarray(w_gu, dtype=np.float64)
-    if w_gu.shape[0] % 64 or w_gu.shape[1] != x.shape[1]:
+    w_joint = np.asarray(w_joint, dtype=np.float64)
+    if w_joint.shape[0] % 64 or w_joint.shape[1] != x.shape[1]:
         raise ValueError("joint matrix must be [2 inter, hidden] with inter a multiple of 32")
-    y = x @ w_gu.T
-    inter = w_gu.shape[0] // 2
+    y = x @ w_joint.T
+    inter = w_joint.shape[0] // 2
     out = np.empty((x.shape[0], inter), dtype=np.float64)
     for b in range(inter // PACK_BLOCK):
         out[:, 32 * b:32 * b + 32] = silu(y[:, 64 * b:64 * b + 32]) * y[:, 64 * b + 32:64 * b + 64]
     return out
+
+
+def pack_gate_up(w_gate: np.ndarray, w_up: np.ndarray) -> np.ndarray:
+    """The library's packed weight format, as a flat array of 2 inter * hidden elements (the layout is part of
+    the interface: it is written out in the header).  The joint matrix is cut into tiles of 256 joint rows x 32
+    hidden entries; tile (tn, ks) starts at element (tn * (hidden / 32) + ks) * 8192; inside a tile, joint row
+    256 tn + r keeps 64 bytes at element r * 32, and its 16-byte piece number s (8 elements) holds the hidden
+    entries 32 ks + 8 (s ^ ((r >> 2) & 3)) .. + 7.  inter a multiple of 128, hidden a multiple of 32."""
+    j = joint_rows(w_gate, w_up)
+    rows, hidden = j.shape
+    if rows % 256 or hidden % 32:
+        raise ValueError("inter must be a multiple of 128 and hidden a multiple of 32")
+    out = np.empty(rows * hidden, dtype=j.dtype)
+    n_ks = hidden // 32
+    for tn in range(rows // 256):
+        for ks in range(n_ks):
+            base = (tn * n_ks + ks) * 8192
+            for r in range(256):
+                for s_ in range(4):
+                    c = s_ ^ ((r >> 2) & 3)
+                    out[base + r * 32 + s_ * 8:base + r * 32 + s_ * 8 + 8] = j[256 * tn + r, 32 * ks + 8 * c:32 * ks + 8 * c + 8]
+    return out
+
+
+def unpack_gate_up(packed: np.ndarray, hidden: int):
+    """Inverse of pack_gate_up, written as the element-wise index formula: (w_gate, w_up)."""
+    packed = np.asarray(packed)
+    rows = packed.size // hidden
+    inter = rows // 2
+    n_ks = hidden // 32
+    w_gate = np.empty((inter, hidden), dtype=packed.dtype)
+    w_up = np.empty((inter, hidden), dtype=packed.dtype)
+    for R in range(rows):
+        tn, r = divmod(R, 256)
+        blk, jj = divmod(R, 64)
+        dst = w_gate if jj < 32 else w_up
+        n = 32 * blk + (jj & 31)
+        for k in range(hidden):
+            ks, kk = divmod(k, 32)
+            c, e = divmod(kk, 8)
+            s_ = c ^ ((r >> 2) & 3)
+            dst[n, k] = packed[(tn * n_ks + ks) * 8192 + r * 32 + s_ * 8 + e]
+    return w_gate, w_up

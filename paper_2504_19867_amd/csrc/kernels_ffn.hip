@@ -3,7 +3,8 @@
 //
 // Paper, Evaluation "Implementation based on DistServe": the first two GEMMs of the gated FFN are
 // fused into one.  With x [T, hidden] and the joint weight matrix w_gu [2 inter, hidden] (rows
-// 64 b .. 64 b + 31 = gate rows 32 b .., rows 64 b + 32 .. 64 b + 63 = the up rows of the same outputs):
+// 64 b .. 64 b + 31 = gate rows 32 b .., rows 64 b + 32 .. 64 b + 63 = the up rows of the same outputs;
+// stored tile by tile, 256 joint rows x 32 hidden entries, in the order the kernel's LDS stage has):
 //     y = x . w_gu^T            out[t, 32 b + j] = silu(y[t, 64 b + j]) * y[t, 64 b + 32 + j]
 // silu(z) = z / (1 + exp(-z)).  bf16 in, fp32 accumulation, one rounding to bf16 at the end.
 //
@@ -107,12 +108,16 @@ __global__ __launch_bounds__(128 * WNW, 2) void ffn_gate_up_kernel(const bf16_t*
 #pragma unroll
   for (int j = 0; j < LPW; ++j) {
     const int ii = wave + WAVES * j;
-    const int s = (ii < A_LOADS ? ii : ii - A_LOADS) * 64 + lane, row = s >> 2, chunk = (s & 3) ^ ((row >> 2) & 3);
-    const int grow = ii < A_LOADS ? min(row, T - 1 - m0) : row;
-    ld_voff[j] = (uint32_t)grow * pitch + (uint32_t)chunk * 16;
+    if (ii < A_LOADS) {
+      const int s = ii * 64 + lane, row = s >> 2, chunk = (s & 3) ^ ((row >> 2) & 3);
+      ld_voff[j] = (uint32_t)min(row, T - 1 - m0) * pitch + (uint32_t)chunk * 16;
+    } else {
+      ld_voff[j] = (uint32_t)((ii - A_LOADS) * 64 + lane) * 16;   // the weights are stored in this very order
+    }
   }
   const char* a_base = (const char*)(x + (size_t)m0 * K);
-  const char* b_base = (const char*)(w + (size_t)n0p * K);
+  // weight tile (joint rows 256 t .., slice ks) is 16 KiB at ((t * K / 32) + ks) * 16 KiB; a 128-row tile is half of one
+  const char* b_base = (const char*)w + ((size_t)(n0p / 256) * (K / BK)) * 16384 + (size_t)(n0p % 256) * 64;
   const int n_slices = K / BK;
   int pt = 0, ct = 0;
   // load instruction j of slice pt; after the last one the slice counts as issued
@@ -120,7 +125,7 @@ __global__ __launch_bounds__(128 * WNW, 2) void ffn_gate_up_kernel(const bf16_t*
     if (pt >= n_slices) return;
     const uint32_t stage = __builtin_amdgcn_readfirstlane(smem_base + (uint32_t)(pt % NSTAGE) * STAGE_BYTES);
     const int ii = wave + WAVES * j;
-    dma16s((ii < A_LOADS ? a_base : b_base) + (size_t)pt * (BK * 2), ld_voff[j], stage + (uint32_t)ii * 1024);
+    dma16s(ii < A_LOADS ? a_base + (size_t)pt * (BK * 2) : b_base + (size_t)pt * 16384, ld_voff[j], stage + (uint32_t)ii * 1024);
     if (j == LPW - 1) ++pt;
   };
   auto produce_one = [&]() __attribute__((always_inline)) {
@@ -223,14 +228,21 @@ __global__ __launch_bounds__(128 * WNW, 2) void ffn_gate_up_kernel(const bf16_t*
     }
 }
 
-// rows of the joint matrix from the two weight matrices: 16-byte pieces, one row of pieces per workgroup row
+// The packed weights from the two weight matrices, one 16-byte piece per thread and step: piece
+// number i of the output lies in tile i / 1024 = (tn, ks), row r = (i % 1024) / 4, slot s = i % 4, and
+// holds the hidden entries 32 ks + 8 (s ^ ((r >> 2) & 3)) .. + 7 of joint row 256 tn + r.
 __global__ __launch_bounds__(256) void ffn_pack_kernel(const uint4* __restrict__ wg, const uint4* __restrict__ wu,
-                                                       uint4* __restrict__ dst, int row_pieces, long n_rows) {
-  for (long r = blockIdx.x; r < n_rows; r += gridDim.x) {
-    const long blk = r >> 6;
-    const int j = (int)(r & 63);
-    const uint4* src = (j < 32 ? wg : wu) + (blk * 32 + (j & 31)) * (long)row_pieces;
-    for (int c = threadIdx.x; c < row_pieces; c += blockDim.x) dst[r * row_pieces + c] = src[c];
+                                                       uint4* __restrict__ dst, int n_ks, long n_pieces) {
+  const long stride = (long)gridDim.x * blockDim.x;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n_pieces; i += stride) {
+    const long tile = i >> 10;
+    const int r = (int)(i & 1023) >> 2, sl = (int)(i & 3);
+    const long tn = tile / n_ks;
+    const int ks = (int)(tile % n_ks);
+    const long R = tn * 256 + r;                // joint row: blocks of 32 gate rows + their 32 up rows
+    const long n = (R >> 6) * 32 + (R & 31);
+    const uint4* src = ((R & 63) < 32 ? wg : wu) + n * (long)(n_ks * 4) + ks * 4 + (sl ^ ((r >> 2) & 3));
+    dst[i] = *src;
   }
 }
 
@@ -257,9 +269,9 @@ hipError_t launch_ffn_gate_up(const void* x, const void* w_gu, void* out, int T,
 }
 
 hipError_t launch_ffn_pack(const void* w_gate, const void* w_up, void* w_gu, int K, int I, hipStream_t stream) {
-  const long n_rows = 2L * I;
-  hipLaunchKernelGGL(ffn_pack_kernel, dim3((unsigned)std::min<long>(n_rows, 4096)), dim3(256), 0, stream, (const uint4*)w_gate,
-                     (const uint4*)w_up, (uint4*)w_gu, K / 8, n_rows);
+  const long n_pieces = 2L * I * K / 8;
+  hipLaunchKernelGGL(ffn_pack_kernel, dim3((unsigned)std::min<long>((n_pieces + 255) / 256, 8192)), dim3(256), 0, stream,
+                     (const uint4*)w_gate, (const uint4*)w_up, (uint4*)w_gu, K / 32, n_pieces);
   return hipGetLastError();
 }
 

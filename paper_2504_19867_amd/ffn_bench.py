@@ -35,15 +35,18 @@ def main():
             w_gu = torch.empty((2 * I, K), device=dev, dtype=torch.bfloat16)
             ctx.ffn_pack_gate_up(PRE, wg, wu, w_gu, K, I)
             ctx.phase_sync(PRE)
+            # decode batches cycle over four copies of the weights (four layers' worth, 0.9 GB): one copy would stay
+            # in the 256 MB memory-side cache from call to call, which a model with many layers never sees
+            w_layers = [w_gu] + ([w_gu.clone() for _ in range(3)] if not quick else [])
             for phase, name, T in ((PRE, "prompt batch 4 x 2048", 8192), (DEC, "decode batch 64", 64), (DEC, "decode batch 256", 256))[:1 if quick else 3]:
                 x = torch.randn((T, K), device=dev, dtype=torch.bfloat16)
                 out = torch.empty((T, I), device=dev, dtype=torch.bfloat16)
-                for _ in range(1 if quick else 3):
-                    ctx.ffn_gate_up(phase, x, w_gu, out, T, K, I)
+                for i in range(1 if quick else 3):
+                    ctx.ffn_gate_up(phase, x, w_layers[i % len(w_layers)] if phase == DEC else w_gu, out, T, K, I)
                 ctx.phase_sync(phase)
                 ctx.phase_kernel_ms(phase)
-                for _ in range(2 if quick else 10):
-                    ctx.ffn_gate_up(phase, x, w_gu, out, T, K, I)
+                for i in range(2 if quick else 12):
+                    ctx.ffn_gate_up(phase, x, w_layers[i % len(w_layers)] if phase == DEC else w_gu, out, T, K, I)
                 ctx.phase_sync(phase)
                 ms = sorted(ctx.phase_kernel_ms(phase))
                 med = ms[len(ms) // 2]
@@ -71,11 +74,17 @@ def concurrent(ctx, dev, total):
     op = torch.empty((8192, I), device=dev, dtype=torch.bfloat16)
     xd = torch.randn((64, K), device=dev, dtype=torch.bfloat16)
     od = torch.empty((64, I), device=dev, dtype=torch.bfloat16)
+    w_layers = [w_gu] + [w_gu.clone() for _ in range(3)]
+    n_dec = [0]
+
+    def dec():
+        ctx.ffn_gate_up(DEC, xd, w_layers[n_dec[0] % 4], od, 64, K, I)
+        n_dec[0] += 1
     res = {}
     for mode in ("solo", "concurrent"):
         for _ in range(2):
             ctx.ffn_gate_up(PRE, xp, w_gu, op, 8192, K, I)
-            ctx.ffn_gate_up(DEC, xd, w_gu, od, 64, K, I)
+            dec()
         ctx.phase_sync(PRE); ctx.phase_sync(DEC)
         ctx.phase_kernel_ms(PRE); ctx.phase_kernel_ms(DEC)
         if mode == "solo":
@@ -83,13 +92,13 @@ def concurrent(ctx, dev, total):
                 ctx.ffn_gate_up(PRE, xp, w_gu, op, 8192, K, I)
             ctx.phase_sync(PRE)
             for _ in range(200):
-                ctx.ffn_gate_up(DEC, xd, w_gu, od, 64, K, I)
+                dec()
             ctx.phase_sync(DEC)
         else:
             for _ in range(8):                   # about 35 decode GEMMs fit beside one prompt-batch GEMM
                 ctx.ffn_gate_up(PRE, xp, w_gu, op, 8192, K, I)
                 for _ in range(30):
-                    ctx.ffn_gate_up(DEC, xd, w_gu, od, 64, K, I)
+                    dec()
             ctx.phase_sync(PRE); ctx.phase_sync(DEC)
         pk, dk = sorted(ctx.phase_kernel_ms(PRE)), sorted(ctx.phase_kernel_ms(DEC))
         res[mode] = (pk[len(pk) // 2], dk[len(dk) // 2])

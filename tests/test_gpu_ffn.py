@@ -47,8 +47,8 @@ def test_gate_up_matches_oracle(T, K, I):
     ctx = S.Context(0)
     xb, wgb, wub = W.ffn_inputs(T, K, I, seed=100 + T)
     out, w_gu = _run(ctx, PRE, xb, wgb, wub)
-    # the joint matrix is a copy: bit for bit the oracle's row order
-    np.testing.assert_array_equal(host_bits(w_gu), F.pack_gate_up(wgb, wub))
+    # the packed weights are a permutation of 16-byte pieces: bit for bit the oracle's layout
+    np.testing.assert_array_equal(host_bits(w_gu).ravel(), F.pack_gate_up(wgb, wub))
     want = F.gate_up(f64(xb), f64(wgb), f64(wub))
     _assert_ffn(host_f64(out), want, f"ffn T={T} K={K} I={I}")
     ctx.close()

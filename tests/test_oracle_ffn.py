@@ -78,15 +78,40 @@ def test_linear_in_up_and_zero_cases():
     np.testing.assert_array_equal(F.gate_up(np.zeros_like(x), wg, wu), np.zeros_like(base))
 
 
-def test_packed_layout_and_single_product_give_the_same():
+def test_joint_rows_and_single_product_give_the_same():
     rng = np.random.default_rng(5)
     x, wg, wu = rng.standard_normal((7, 16)), rng.standard_normal((96, 16)), rng.standard_normal((96, 16))
-    w = F.pack_gate_up(wg, wu)
+    w = F.joint_rows(wg, wu)
     assert w.shape == (192, 16)
     # row order: 32 gate rows, the 32 up rows of the same outputs, and so on
     for b in range(3):
         np.testing.assert_array_equal(w[64 * b:64 * b + 32], wg[32 * b:32 * b + 32])
         np.testing.assert_array_equal(w[64 * b + 32:64 * b + 64], wu[32 * b:32 * b + 32])
-    np.testing.assert_allclose(F.gate_up_packed(x, w), F.gate_up(x, wg, wu), rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(F.gate_up_joint(x, w), F.gate_up(x, wg, wu), rtol=1e-13, atol=1e-15)
     with pytest.raises(ValueError):
-        F.pack_gate_up(wg[:40], wu[:40])
+        F.joint_rows(wg[:40], wu[:40])
+
+
+def test_packed_format_places_elements_where_the_header_says():
+    # every element carries its own coordinates, so a misplaced one is seen at once
+    inter, hidden = 256, 96
+    wg = (np.arange(inter)[:, None] * 1000 + np.arange(hidden)[None, :]).astype(np.int64)
+    wu = wg + 500000
+    p = F.pack_gate_up(wg, wu)
+    assert p.shape == (2 * inter * hidden,)
+    assert sorted(p.tolist()) == sorted(wg.ravel().tolist() + wu.ravel().tolist())          # a permutation
+    n_ks = hidden // 32
+    # spot checks written out by hand: joint row 0 = gate row 0; its piece 0 holds hidden 0..7 (r >> 2 = 0)
+    np.testing.assert_array_equal(p[0:8], wg[0, 0:8])
+    # joint row 4 (gate row 4): (r >> 2) & 3 = 1, so piece 0 holds hidden 8..15 and piece 1 hidden 0..7
+    np.testing.assert_array_equal(p[4 * 32:4 * 32 + 8], wg[4, 8:16])
+    np.testing.assert_array_equal(p[4 * 32 + 8:4 * 32 + 16], wg[4, 0:8])
+    # joint row 32 is up row 0; tile (0, ks = 1) starts at element 8192
+    np.testing.assert_array_equal(p[8192 + 32 * 32:8192 + 32 * 32 + 8], wu[0, 32:40])
+    # joint row 256 opens tile row tn = 1: gate row 128, at element (1 * n_ks + 0) * 8192
+    np.testing.assert_array_equal(p[n_ks * 8192:n_ks * 8192 + 8], wg[128, 0:8])
+    g2, u2 = F.unpack_gate_up(p, hidden)
+    np.testing.assert_array_equal(g2, wg)
+    np.testing.assert_array_equal(u2, wu)
+    with pytest.raises(ValueError):
+        F.pack_gate_up(wg[:64], wu[:64])
