@@ -207,7 +207,7 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(const char* __restrict__
     const int t = i & 15, c = i >> 4;
     if (t >= d.t_begin && t < d.t_end) {
       const size_t off = natural ? (size_t)t * dk * 2 + (size_t)c * 16 : ((size_t)(c * 16 + t) << 4);
-      *(uint4*)(k_out + ((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dk + c * 8) = *(const uint4*)(tile + off);
+      *(uint4*)(k_out + ((size_t)(d.src_row + t - d.t_begin) * Hkv + g) * dk + c * 8) = load_once(tile + off);
     }
   }
   if (v_out == nullptr) return;
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(const char* __restrict__
   const int v_items = (dv >> 5) * 64;               // 16-byte pieces of the tile: (d/32, token quad, d%16)
   for (int i = threadIdx.x; i < v_items; i += blockDim.x) {
     const int m = i & 15, c4 = (i >> 4) & 3, blk2 = i >> 6;
-    const uint4 pk = *(const uint4*)(vt + ((size_t)((blk2 * 4 + c4) * 16 + m) << 3));
+    const uint4 pk = load_once(vt + ((size_t)((blk2 * 4 + c4) * 16 + m) << 3));
     const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w};
 #pragma unroll
     for (int e = 0; e < 8; ++e) {                   // element e = (d/16)%2 * 4 + token%4
