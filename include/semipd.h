@@ -297,6 +297,13 @@ int spd_phase_stream(spd_ctx* ctx, int phase, void** hip_stream_out);
  * timed only while timing is on (spd_set_kernel_timing); otherwise SPD_ESTATE. */
 int spd_phase_last_ms(spd_ctx* ctx, int phase, float* ms);
 
+/* Two environment variables, read at every step, override choices the library otherwise makes
+ * itself; they exist for measurements and change no result:
+ *   SPD_PREFILL_PERSISTENT=0|1  launch the prefill kernel with one workgroup per work item (0) or
+ *                               with one persistent workgroup per compute unit (1) regardless of
+ *                               the partition;
+ *   SPD_DECODE_CHUNK_TILES=n    fix the split-K chunk of the decode kernels to n 16-token tiles. */
+
 /* Measurement aid.  With timing on, each step is bracketed by HIP events (spd_phase_last_ms)
  * and, separately, so are its attention kernel(s) (not the
  * block-table upload or the page write) with HIP events on the phase's stream; the last
