@@ -38,8 +38,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int BK = 32;                          // hidden entries per slice
-constexpr int NSTAGE = 4, PD = NSTAGE - 1;
-constexpr int LPW = 4;                          // 1 KiB load instructions per wave per slice: two of x, two of the weights
 
 __device__ inline uint32_t cvt_bf16(float a) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, a}, bf16x2)) & 0xffffu;
@@ -51,18 +49,21 @@ __device__ inline void dma16s(const void* sbase, uint32_t voff, uint32_t lds_byt
 }
 #define SPD_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
 
-// MB: 32-token blocks per wave; WNW: waves along the joint columns.  The waves form a 2 x WNW grid,
-// each with 32 MB tokens x 64 joint columns; the workgroup's tile is 64 MB tokens x 64 WNW joint columns.
-// <4, 4>: 256 x 256 for prompt batches; <2, 2>: 128 x 128, four waves, two workgroups per CU, for
-// batches of up to 128 tokens, where the product is bound by reading the weights once and many
-// small workgroups keep more of them in flight.
-template <int MB, int WNW>
+// MB: 32-token blocks per wave; WNW: waves along the joint columns; NSTAGE: LDS ring.  The waves form a
+// 2 x WNW grid, each with 32 MB tokens x 64 joint columns; the workgroup's tile is 64 MB tokens x 64 WNW
+// joint columns.
+// <4, 4, 4>: 256 x 256 for prompt batches.  For small batches the product is bound by reading the
+// weights once, and what counts is how many weight bytes a CU keeps in flight: <2, 2, 4>: 128 x 128,
+// four waves, two workgroups per CU, for up to 128 tokens; <1, 2, 6>: 64 x 128 with a ring of six
+// 12 KiB stages, of which 8 KiB are weights, two workgroups per CU, for up to 64 tokens.
+template <int MB, int WNW, int NSTAGE>
 __global__ __launch_bounds__(128 * WNW, 2) void ffn_gate_up_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
                                                                    bf16_t* __restrict__ out, int T, int K, int I, int tiles_m,
                                                                    int tiles_n, int xcds) {
-  constexpr int WAVES = 2 * WNW, BM = 64 * MB, BNP = 64 * WNW;
+  constexpr int WAVES = 2 * WNW, BM = 64 * MB, BNP = 64 * WNW, PD = NSTAGE - 1;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BNP * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
-  static_assert((A_BYTES + B_BYTES) / 1024 == LPW * WAVES && A_BYTES / 1024 == 2 * WAVES, "two x and two weight loads per wave");
+  constexpr int LPW = (A_BYTES + B_BYTES) / 1024 / WAVES;   // 1 KiB load instructions per wave per slice
+  static_assert((A_BYTES + B_BYTES) / 1024 == LPW * WAVES && (A_BYTES / 1024) % WAVES == 0, "loads divide evenly over the waves");
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -176,7 +177,9 @@ __global__ __launch_bounds__(128 * WNW, 2) void ffn_gate_up_kernel(const bf16_t*
   // this wave's loads of slice s are done when at most (slices issued after it) * LPW remain
   auto wait_slice = [&](int s) __attribute__((always_inline)) {
     const int later = pt - s - 1;
-    if (later >= 2) SPD_WAIT_VMCNT(2 * LPW);
+    if (NSTAGE > 5 && later >= 4) SPD_WAIT_VMCNT(4 * LPW);
+    else if (NSTAGE > 4 && later == 3) SPD_WAIT_VMCNT(3 * LPW);
+    else if (later >= 2) SPD_WAIT_VMCNT(2 * LPW);
     else if (later == 1) SPD_WAIT_VMCNT(LPW);
     else SPD_WAIT_VMCNT(0);
   };
@@ -248,13 +251,13 @@ __global__ __launch_bounds__(256) void ffn_pack_kernel(const uint4* __restrict__
 
 }  // namespace
 
-template <int MB, int WNW>
+template <int MB, int WNW, int NSTAGE>
 static hipError_t launch_tiles(const void* x, const void* w_gu, void* out, int T, int K, int I, int xcds, hipStream_t stream) {
   constexpr int BM = 64 * MB, BNP = 64 * WNW;
   const int tiles_m = (T + BM - 1) / BM, tiles_n = 2 * I / BNP;
   if (tiles_n < xcds) xcds = 1;
   const int per = xcds > 1 ? ((tiles_n + xcds - 1) / xcds) * tiles_m : tiles_m * tiles_n;
-  hipLaunchKernelGGL((ffn_gate_up_kernel<MB, WNW>), dim3((unsigned)(per * xcds)), dim3(128 * WNW), 0, stream, (const bf16_t*)x,
+  hipLaunchKernelGGL((ffn_gate_up_kernel<MB, WNW, NSTAGE>), dim3((unsigned)(per * xcds)), dim3(128 * WNW), 0, stream, (const bf16_t*)x,
                      (const bf16_t*)w_gu, (bf16_t*)out, T, K, I, tiles_m, tiles_n, xcds);
   return hipGetLastError();
 }
@@ -264,8 +267,9 @@ hipError_t launch_ffn_gate_up(const void* x, const void* w_gu, void* out, int T,
   // small batches are bound by reading the weights: the small tile where the large one would leave
   // half of the share's compute units without a workgroup
   const int large_tiles = ((T + 255) / 256) * (2 * I / 256);
-  if (T <= 128 || (T <= 256 && 2 * large_tiles <= cus)) return launch_tiles<2, 2>(x, w_gu, out, T, K, I, xcds, stream);
-  return launch_tiles<4, 4>(x, w_gu, out, T, K, I, xcds, stream);
+  if (T <= 64) return launch_tiles<1, 2, 6>(x, w_gu, out, T, K, I, xcds, stream);
+  if (T <= 128 || (T <= 256 && 2 * large_tiles <= cus)) return launch_tiles<2, 2, 4>(x, w_gu, out, T, K, I, xcds, stream);
+  return launch_tiles<4, 4, 4>(x, w_gu, out, T, K, I, xcds, stream);
 }
 
 hipError_t launch_ffn_pack(const void* w_gate, const void* w_up, void* w_gu, int K, int I, hipStream_t stream) {
