@@ -325,7 +325,9 @@ int spd_phase_copy(spd_ctx* ctx, int phase, void* dst, const void* src, uint64_t
  * a new (x, y) is prepared first and adopted late (delayed switching), and each worker
  * adopts it at its own iteration boundary without waiting for the other (asynchronous
  * switching).  Here (x, y) are CU counts.  Each is rounded to the nearest multiple of the
- * granularity, at least one granule, at most all CUs.  Prefill takes CUs from the low end of
+ * granularity, at least one granule, at most all CUs; if the two requested counts sum to no more
+ * than the total (disjoint shares) and the rounded ones would overlap, decode gets what prefill
+ * leaves.  Prefill takes CUs from the low end of
  * the mask, decode from the high end; they overlap only when the counts sum above the total.
  * The call prepares (creates or re-uses) the two CU-masked streams and stages them as
  * pending; it never blocks on GPU work and never touches the pool.  Each phase switches to

@@ -33,6 +33,11 @@ extern "C" int spd_partition_masks(int total_cus, int granularity, int prefill_c
   if (prefill_cus <= 0 || decode_cus <= 0 || !prefill_words || !decode_words) return SPD_EINVAL;
   int p = round_cus(prefill_cus, granularity, total_cus);
   int d = round_cus(decode_cus, granularity, total_cus);
+  // a request for disjoint shares stays disjoint after the rounding
+  if ((int64_t)prefill_cus + decode_cus <= total_cus && p + d > total_cus) {
+    if (p > total_cus - granularity) p = total_cus - granularity;
+    d = total_cus - p;
+  }
   int words = (total_cus + 31) / 32;
   memset(prefill_words, 0, sizeof(uint32_t) * words);
   memset(decode_words, 0, sizeof(uint32_t) * words);

@@ -112,3 +112,37 @@ def test_llama3_8b_shape_sampled():
     want = F.gate_up(f64(xb[rows]), f64(wgb), f64(wub))
     _assert_ffn(host_f64(out[torch.from_numpy(rows).to(DEV)]), want, "ffn llama-3-8b sampled rows")
     ctx.close()
+
+
+def test_prompt_and_decode_batches_at_the_same_time_on_disjoint_partitions():
+    """The paper's setting for this step: a prompt batch on the prefill partition while the decode partition runs
+    decode batches; every launch gives the bits it gives alone."""
+    ctx = S.Context(0)
+    total = ctx.device_info()[0]
+    K, I = 512, 1024
+    xpb, wgb, wub = W.ffn_inputs(1500, K, I, seed=31)
+    xdb, _, _ = W.ffn_inputs(48, K, I, seed=32)
+    ref_p, w_gu = _run(ctx, PRE, xpb, wgb, wub)
+    ref_p = host_bits(ref_p)
+    xd = dev_bf16(xdb)
+    od = torch.full((48, I), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ctx.ffn_gate_up(DEC, xd, w_gu, od, 48, K, I)
+    ctx.phase_sync(DEC)
+    ref_d = host_bits(od)
+    _assert_ffn(host_f64(od), F.gate_up(f64(xdb), f64(wgb), f64(wub)), "ffn decode batch")
+    ctx.set_partition(total // 2, total // 2)
+    xp = dev_bf16(xpb)
+    outs_p = [torch.full((1500, I), float("nan"), dtype=torch.bfloat16, device=DEV) for _ in range(3)]
+    outs_d = [torch.full((48, I), float("nan"), dtype=torch.bfloat16, device=DEV) for _ in range(12)]
+    for i in range(3):                            # both streams fill up before either drains
+        ctx.ffn_gate_up(PRE, xp, w_gu, outs_p[i], 1500, K, I)
+        for j in range(4):
+            ctx.ffn_gate_up(DEC, xd, w_gu, outs_d[4 * i + j], 48, K, I)
+    ctx.phase_sync(PRE)
+    ctx.phase_sync(DEC)
+    assert ctx.get_partition()[:2] == (total // 2, total // 2)
+    for o in outs_p:
+        np.testing.assert_array_equal(host_bits(o), ref_p)
+    for o in outs_d:
+        np.testing.assert_array_equal(host_bits(o), ref_d)
+    ctx.close()

@@ -312,6 +312,20 @@ def test_masked_streams_stay_on_their_cus():
 
 
 # ----------------------------------------------------------------------------- config 2 at full size
+def test_partition_sizes_are_whole_rows_of_shader_arrays():
+    """On the device, shares are rounded to one compute unit per shader array and XCD (32 CUs): what is beyond
+    such a row adds no throughput, the dispatcher deals workgroups to the shader arrays in turn."""
+    ctx = S.Context(0)
+    total, xcds, gran = ctx.device_info()
+    assert gran == 4 * xcds and total % gran == 0
+    ctx.set_partition(80, 176)
+    pa, da, pp, dp = ctx.get_partition()
+    assert (pp, dp) == (96, 160) and pp % gran == 0 and dp % gran == 0
+    ctx.set_partition(1, total)
+    assert ctx.get_partition()[2:] == (gran, total)
+    ctx.close()
+
+
 def test_c2_full_size_sampled_against_oracle():
     cfg = W.get_config("c2")
     L = cfg.layer

@@ -190,6 +190,15 @@ def test_partition_masks_disjoint_and_balanced(p, d):
         assert len(set(per_xcd)) == 1
 
 
+def test_partition_rounding_keeps_disjoint_requests_disjoint():
+    for p, d in [(80, 176), (112, 144), (16, 240), (240, 16), (250, 6), (1, 255)]:
+        pm, dm, pr, dr = S.partition_masks(256, 32, p, d)
+        assert pr % 32 == 0 and dr % 32 == 0 and pr >= 32 and dr >= 32 and pr + dr <= 256, (p, d, pr, dr)
+        assert not any(a & b for a, b in zip(pm, dm))
+    assert S.partition_masks(256, 32, 80, 176)[2:] == (96, 160)
+    assert S.partition_masks(256, 32, 200, 200)[2:] == (192, 192)       # asked to overlap: each rounded on its own
+
+
 def test_partition_masks_oversubscription_overlaps():
     pm, dm, pr, dr = S.partition_masks(256, 8, 256, 256)      # the paper's (100, 100) setting
     assert pr == dr == 256 and bits(pm) == bits(dm) == set(range(256))
