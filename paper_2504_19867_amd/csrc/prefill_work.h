@@ -90,13 +90,24 @@ inline void build_prefill_chains(const int32_t* cu_seqlens, const int32_t* prefi
   }
   std::vector<std::vector<Item>> chains((size_t)n_blocks);
   for (int x = 0; x < xcds; ++x) {
+    // Unit after unit (in the order the XCD took them), each unit's items longest-first onto the chain
+    // with the least load so far: every chain then holds about the same weight of EVERY unit, so the
+    // chains of an XCD pass from one unit to the next at about the same time and the XCD's L2 has to
+    // hold one or two units' K, V, not all of them.  (Dealt over all units at once the chains were as
+    // well balanced in total, but drifted apart unit by unit, and K, V crossed HBM four times.)
     std::vector<Item>& items = xq[(size_t)x];
-    std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.weight > b.weight; });
     std::vector<long> load((size_t)per_xcd, 0);
-    for (const Item& it : items) {
-      const int c = (int)(std::min_element(load.begin(), load.end()) - load.begin());
-      load[(size_t)c] += it.weight;
-      chains[(size_t)(c * xcds + x)].push_back(it);          // workgroup id = chain slot * xcds + xcd
+    size_t a = 0;
+    while (a < items.size()) {
+      size_t b = a;
+      while (b < items.size() && items[b].unit == items[a].unit) ++b;
+      std::stable_sort(items.begin() + (long)a, items.begin() + (long)b, [](const Item& p, const Item& q) { return p.weight > q.weight; });
+      for (size_t i = a; i < b; ++i) {
+        const int c = (int)(std::min_element(load.begin(), load.end()) - load.begin());
+        load[(size_t)c] += items[i].weight;
+        chains[(size_t)(c * xcds + x)].push_back(items[i]);          // workgroup id = chain slot * xcds + xcd
+      }
+      a = b;
     }
   }
   work.clear();
