@@ -27,10 +27,13 @@
 //
 // K and V tiles of 64 keys stream from global memory straight into a ring of LDS stages with
 // global_load_lds_dwordx4 (no register staging, no LDS stores), ahead of the compute; one
-// s_barrier per pair of tiles where the ring has four stages (one per tile with three).  K rows are read back with 16-byte reads in A-operand order; V stays
-// in its natural [key][dim] order and the transposition that the second product needs is done
-// by the LDS transpose read ds_read_b64_tr_b16.  Both tiles are XOR-swizzled at 16-byte
-// granularity against bank conflicts.
+// s_barrier per pair of tiles where the ring has four stages (one per tile with three).  K rows
+// are read back with 16-byte reads in A-operand order; V stays in its natural [key][dim] order
+// and the transposition that the second product needs is done by the LDS transpose read
+// ds_read_b64_tr_b16.  Both tiles are XOR-swizzled at 16-byte granularity against bank conflicts.
+//
+// The softmax keeps a reference per query that is moved to the running maximum only when a row sum
+// shows that it must be (an item's first tile, or scores that have outgrown it by 2^60).
 #include "internal.h"
 #include <type_traits>
 
@@ -125,7 +128,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     slot_of(j, row, coff, pitch);
     ld_voff[j] = (uint32_t)row * pitch + (uint32_t)coff;
   }
-  // ---- producer: the tile loads run PD tiles ahead of the compute, across the items of the chain.
+  // ---- producer: the tile loads run ahead of the compute (a pair of tiles, or PD tiles where the
+  // ring has three stages), across the items of the chain.
   // pt counts the tiles issued so far (tile number pt goes to stage pt % NSTAGE).
   int p_it = it, p_kt = 0, p_n = 0, p_kv_len = 0, pt = 0;
   const char *p_kb = nullptr, *p_vb = nullptr;
