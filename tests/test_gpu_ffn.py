@@ -146,3 +146,18 @@ def test_prompt_and_decode_batches_at_the_same_time_on_disjoint_partitions():
     for o in outs_d:
         np.testing.assert_array_equal(host_bits(o), ref_d)
     ctx.close()
+
+
+def test_random_shapes():
+    """Seeded random (tokens, hidden, inter) within the interface's conditions: every tile instance, ragged token
+    counts, hidden sizes that are not a multiple of the 64-wide register pipeline's unroll."""
+    rng = np.random.default_rng(77)
+    ctx = S.Context(0)
+    for case in range(12):
+        T = int(rng.integers(1, 700))
+        K = 32 * int(rng.integers(1, 33))
+        I = 128 * int(rng.integers(1, 7))
+        xb, wgb, wub = W.ffn_inputs(T, K, I, seed=500 + case)
+        out, _ = _run(ctx, (PRE, DEC)[case % 2], xb, wgb, wub)
+        _assert_ffn(host_f64(out), F.gate_up(f64(xb), f64(wgb), f64(wub)), f"ffn random case {case}: T={T} K={K} I={I}")
+    ctx.close()
