@@ -38,7 +38,8 @@ enum {
   SPD_ENOMEM = -2, /* pool exhausted: fewer free blocks than the call needs                 */
   SPD_ENOENT = -3, /* unknown request id                                                    */
   SPD_EHIP = -5,   /* a HIP call failed; spd_last_hip_error() has its code                  */
-  SPD_ESTATE = -6  /* call not valid in this state (e.g. a step on a host-only context)     */
+  SPD_ESTATE = -6, /* call not valid in this state (e.g. a step on a host-only context)     */
+  SPD_ETOOBIG = -7 /* spd_decode_step_noalloc: the batch needs more than its fixed scratch   */
 };
 
 enum { SPD_PHASE_PREFILL = 0, SPD_PHASE_DECODE = 1 };
@@ -201,6 +202,29 @@ typedef struct {
   const struct spd_rope_config* rope; /* NULL, or: q and k_new are given before RoPE (see below) */
 } spd_decode_batch;
 int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* batch);
+
+/* The decode step for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * results as spd_decode_step, but the call allocates and frees nothing on the device or in pinned
+ * memory (no hipMalloc / hipHostMalloc / hipFree, no event or stream creation): the device twin of
+ * the step's metadata (context lengths, block tables, work items, append descriptors, RoPE
+ * frequencies) and the workspace (split-K partials, rotated queries) lie in a static device array of
+ * 33 MiB that every GPU the library runs on holds from the library's load to the end of the process
+ * (its address is resolved once per device in spd_ctx_create), and the pinned staging ring is the one
+ * spd_ctx_create made.  Limits (spd_noalloc_limits): 256 KiB of metadata per step, i.e.
+ * 4 n_req (1 + pages of the longest context) + 8 work items + 32 n_req (append) bytes, and 32 MiB of
+ * workspace, i.e. 4 n_req n_q_heads chunks (dim_v + 2) + 2 n_req n_q_heads dim_k (rope) bytes, where
+ * chunks is the split-K count the library picks (about 6 workgroups per compute unit of the decode
+ * share).  A batch beyond either limit is refused with SPD_ETOOBIG and nothing is enqueued.  Kernel
+ * timing (spd_set_kernel_timing) is not recorded for these steps.
+ * The array is shared by every context and every call on that GPU and keeps the last call's contents
+ * (nothing in it has to start at zero: each step writes every partial it later reads).  Steps of one
+ * decode phase run in stream order and may follow one another freely, also mixed with spd_decode_step;
+ * calls on the same GPU from two contexts, or from two processes' worth of streams, that overlap in
+ * time race on the array and must be serialised by the caller. */
+int spd_decode_step_noalloc(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* batch);
+/* The two limits above, in bytes (either pointer may be NULL). */
+int spd_noalloc_limits(uint64_t* metadata_bytes, uint64_t* workspace_bytes);
 
 /* ------------------------------------------------------------------ the step before attention */
 

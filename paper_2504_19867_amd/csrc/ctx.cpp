@@ -96,10 +96,23 @@ extern "C" int spd_ctx_create(int device, spd_ctx** out) {
       if (rc == SPD_OK && e == hipSuccess) e = hipEventCreate(&s.ev_end);
       if (rc == SPD_OK && e == hipSuccess) e = hipEventCreateWithFlags(&s.ev_switch, hipEventDisableTiming);
       if (rc == SPD_OK && e == hipSuccess) e = hipEventCreateWithFlags(&s.ev_cross, hipEventDisableTiming);
+      // The decode phase's staging ring exists from the start, with the capacity the entry point that
+      // allocates nothing works with; each slot has a device twin of its own and one in the scratch array.
+      if (rc == SPD_OK && e == hipSuccess && ph == SPD_PHASE_DECODE) {
+        rc = scratch_resolve(device, &c->scratch);
+        for (int i = 0; rc == SPD_OK && e == hipSuccess && i < 4; ++i) {
+          spd_stage& st = s.ring[i];
+          e = hipHostMalloc((void**)&st.host, NOALLOC_STAGE_BYTES, hipHostMallocDefault);
+          if (e == hipSuccess) e = hipMalloc((void**)&st.dev, NOALLOC_STAGE_BYTES);
+          if (e == hipSuccess) e = hipEventCreateWithFlags(&st.done, hipEventDisableTiming);
+          st.cap = NOALLOC_STAGE_BYTES;
+          st.dev_static = c->scratch + (size_t)i * NOALLOC_STAGE_BYTES;
+        }
+      }
       if (rc != SPD_OK || e != hipSuccess) {
         if (e != hipSuccess) hip_fail(e);
         spd_ctx_destroy(c);
-        return SPD_EHIP;
+        return rc != SPD_OK && rc != SPD_EHIP ? rc : SPD_EHIP;
       }
     }
   }
@@ -207,7 +220,7 @@ int phase_enter(spd_ctx* ctx, int phase, hipStream_t* stream_out) {
   return SPD_OK;
 }
 
-int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out) {
+int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out, bool may_alloc) {
   spd_phase_state& s = ctx->phase[phase];
   spd_stage& st = s.ring[s.ring_pos];
   if (st.in_flight) {
@@ -218,6 +231,7 @@ int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out) {
     if (e != hipSuccess) return hip_fail(e);
     st.in_flight = false;
   }
+  if (!may_alloc && (!st.done || st.cap < bytes || !st.dev_static)) return SPD_ETOOBIG;
   if (!st.done) SPD_HIP(hipEventCreateWithFlags(&st.done, hipEventDisableTiming));
   if (st.cap < bytes) {
     size_t cap = std::max<size_t>(256 * 1024, st.cap);
@@ -239,7 +253,7 @@ int stage_host_as_device(spd_stage* st, void** out) {
   return SPD_OK;
 }
 
-int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream, bool copy) {
+int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream, bool copy, char* dev) {
   spd_phase_state& s = ctx->phase[phase];
   // The step's metadata crosses to the device with a small copy kernel on the phase's own stream
   // (pinned host memory is device-readable).  hipMemcpyAsync would put it on a copy path that the
@@ -248,7 +262,7 @@ int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream
   if (copy) {
     void* host_dev = nullptr;
     SPD_HIP(hipHostGetDevicePointer(&host_dev, st->host, 0));
-    SPD_HIP(launch_copy(st->dev, host_dev, (bytes + 15) & ~(size_t)15, 1, stream));
+    SPD_HIP(launch_copy(dev ? dev : st->dev, host_dev, (bytes + 15) & ~(size_t)15, 1, stream));
   }
   SPD_HIP(hipEventRecord(st->done, stream));
   st->in_flight = true;

@@ -79,6 +79,13 @@ struct PrefillWork {
   int32_t q_off;     // position of query row 0 in the request = number of cached tokens before it
 };
 
+// The entry point that allocates nothing keeps its device-side working memory in one static device
+// array (noalloc.hip): four metadata twins (one per slot of the decode phase's staging ring), then the
+// split-K partials and the rotated queries.
+constexpr size_t NOALLOC_STAGE_BYTES = 256u << 10;
+constexpr size_t NOALLOC_WS_BYTES = 32u << 20;
+constexpr size_t SCRATCH_BYTES = 4 * NOALLOC_STAGE_BYTES + NOALLOC_WS_BYTES;
+
 extern thread_local int g_last_hip_error;
 inline int hip_fail(hipError_t e) { g_last_hip_error = (int)e; return SPD_EHIP; }
 #define SPD_HIP(expr) do { hipError_t _e = (expr); if (_e != hipSuccess) return ::spd::hip_fail(_e); } while (0)
@@ -103,6 +110,7 @@ struct spd_stage {          // pinned host buffer + device twin, reused round-ro
   char* host = nullptr;
   char* dev = nullptr;
   size_t cap = 0;
+  char* dev_static = nullptr;   // this slot's metadata twin inside the static scratch array (decode phase)
   hipEvent_t done = nullptr;
   bool in_flight = false;
 };
@@ -134,14 +142,19 @@ struct spd_ctx {
   std::map<std::vector<uint32_t>, hipStream_t> stream_cache;
   spd_phase_state phase[2];
   bool kernel_timing = false;
+  char* scratch = nullptr;             // this device's copy of the static scratch array (noalloc.hip)
 };
 
 namespace spd {
 // host helpers (ctx.cpp)
 int phase_enter(spd_ctx* ctx, int phase, hipStream_t* stream_out);   // adopt pending stream
-int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out);
+// may_alloc = false: SPD_ETOOBIG instead of growing the slot's buffers
+int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out, bool may_alloc = true);
+int scratch_resolve(int device, char** out);   // noalloc.hip: address of `device`'s copy of the scratch array
 // copy = false: the caller has already launched a kernel that copies host -> dev (see launch_kv_write)
-int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream, bool copy = true);
+// dev: the device twin to copy to (null: the slot's own st->dev)
+int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream, bool copy = true,
+                 char* dev = nullptr);
 int stage_host_as_device(spd_stage* st, void** out);   // device-readable address of the pinned host buffer
 int workspace_reserve(spd_ctx* ctx, int phase, size_t bytes, char** out);
 int kernel_timing_mark(spd_ctx* ctx, int phase, int which, hipStream_t stream);   // which: 0 begin, 1 end

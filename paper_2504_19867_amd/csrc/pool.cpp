@@ -146,6 +146,7 @@ extern "C" const char* spd_strerror(int status) {
     case SPD_ENOENT: return "unknown request id";
     case SPD_EHIP: return "HIP call failed";
     case SPD_ESTATE: return "call not valid in this state";
+    case SPD_ETOOBIG: return "batch exceeds the fixed scratch memory of the entry point that allocates nothing";
     default: return "unknown status";
   }
 }

@@ -285,7 +285,9 @@ static int decode_chunk_units(spd_phase_state& ps, const int32_t* ctx_lens, int 
   return (int)std::min<int64_t>(std::max<int64_t>(c, 16), 1 << 20);
 }
 
-extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* b) {
+// noalloc: the variant that allocates nothing.  Metadata twins and workspace lie in the static scratch
+// array, the staging ring is used as spd_ctx_create made it, no timing events are recorded.
+static int decode_step_impl(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* b, bool noalloc) {
   if (!ctx || !pool || pool->ctx != ctx || !b || b->n_req <= 0 || !b->req_ids || !b->ctx_lens) return SPD_EINVAL;
   if (!b->q || !b->out || b->n_q_heads <= 0) return SPD_EINVAL;
   const PoolGeom& g = pool->geom;
@@ -346,14 +348,21 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
   size_t off_w = align16(off_desc + (append ? sizeof(TileDesc) * (size_t)B : 0));
   size_t bytes = off_w + (b->rope ? sizeof(double) * (size_t)(b->rope->rotary_dim / 2) : 0);
   spd_stage* st;
-  if ((rc = stage_acquire(ctx, SPD_PHASE_DECODE, bytes, &st)) != SPD_OK) return rc;
+  if (noalloc && bytes > NOALLOC_STAGE_BYTES) return SPD_ETOOBIG;
+  if ((rc = stage_acquire(ctx, SPD_PHASE_DECODE, bytes, &st, !noalloc)) != SPD_OK) return rc;
+  char* const sdev = noalloc ? st->dev_static : st->dev;          // device twin of the step's metadata
+  const bool timing = ctx->kernel_timing && !noalloc;
   char* ws = nullptr;
   size_t ws_o_bytes = max_chunks > 1 ? align16(sizeof(float) * (size_t)B * b->n_q_heads * max_chunks * g.dv) : 0;
   size_t ws_ml_bytes = max_chunks > 1 ? align16(sizeof(float) * (size_t)B * b->n_q_heads * max_chunks * 2) : 0;
   size_t ws_q_bytes = b->rope ? (size_t)B * b->n_q_heads * g.dk * 2 : 0;      // the rotated query
-  if (ws_o_bytes + ws_ml_bytes + ws_q_bytes > 0 &&
-      (rc = workspace_reserve(ctx, SPD_PHASE_DECODE, ws_o_bytes + ws_ml_bytes + ws_q_bytes, &ws)) != SPD_OK)
+  if (noalloc) {
+    if (ws_o_bytes + ws_ml_bytes + ws_q_bytes > NOALLOC_WS_BYTES) return SPD_ETOOBIG;
+    ws = ctx->scratch + 4 * NOALLOC_STAGE_BYTES;
+  } else if (ws_o_bytes + ws_ml_bytes + ws_q_bytes > 0 &&
+             (rc = workspace_reserve(ctx, SPD_PHASE_DECODE, ws_o_bytes + ws_ml_bytes + ws_q_bytes, &ws)) != SPD_OK) {
     return rc;
+  }
   char* ws_q = b->rope ? ws + ws_o_bytes + ws_ml_bytes : nullptr;
   if (b->rope) rope_frequencies(b->rope, (double*)(st->host + off_w));
 
@@ -392,32 +401,46 @@ extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_ba
       }
     }
   }
-  if (ctx->kernel_timing) SPD_HIP(hipEventRecord(ds.ev_start, stream));
-  if ((rc = stage_commit(ctx, SPD_PHASE_DECODE, st, bytes, stream)) != SPD_OK) return rc;
+  if (timing) SPD_HIP(hipEventRecord(ds.ev_start, stream));
+  if ((rc = stage_commit(ctx, SPD_PHASE_DECODE, st, bytes, stream, true, sdev)) != SPD_OK) return rc;
   const void* att_q = b->q;
   if (b->rope) {
-    SPD_HIP(launch_rope_append(g, pool->base, (const TileDesc*)(st->dev + off_desc), (const int32_t*)st->dev, B, b->q, ws_q,
+    SPD_HIP(launch_rope_append(g, pool->base, (const TileDesc*)(sdev + off_desc), (const int32_t*)sdev, B, b->q, ws_q,
                                b->n_q_heads, g.dk, append ? b->k_new : nullptr, append ? b->v_new : nullptr,
                                b->rope->rotary_dim, b->rope->rotary_offset, b->rope->interleaved != 0,
-                               (const double*)(st->dev + off_w), stream));
+                               (const double*)(sdev + off_w), stream));
     att_q = ws_q;
   } else if (append) {
-    SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(st->dev + off_desc), B, b->k_new, b->v_new, stream));
+    SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(sdev + off_desc), B, b->k_new, b->v_new, stream));
   }
-  if ((rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 0, stream)) != SPD_OK) return rc;
+  if (timing && (rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 0, stream)) != SPD_OK) return rc;
   if (mla)
-    SPD_HIP(launch_decode_mla(g, pool->base, att_q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
-                              bt_stride, st->dev + off_items, n_items, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks,
+    SPD_HIP(launch_decode_mla(g, pool->base, att_q, b->out, (const int32_t*)sdev, (const int32_t*)(sdev + off_bt),
+                              bt_stride, sdev + off_items, n_items, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks,
                               (float*)(max_chunks > 1 ? ws : nullptr), (float*)(max_chunks > 1 ? ws + ws_o_bytes : nullptr), stream));
   else
-    SPD_HIP(launch_decode_gqa(g, pool->base, att_q, b->out, (const int32_t*)st->dev, (const int32_t*)(st->dev + off_bt),
-                              bt_stride, st->dev + off_items, n_items, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks,
+    SPD_HIP(launch_decode_gqa(g, pool->base, att_q, b->out, (const int32_t*)sdev, (const int32_t*)(sdev + off_bt),
+                              bt_stride, sdev + off_items, n_items, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks,
                               (float*)(max_chunks > 1 ? ws : nullptr), (float*)(max_chunks > 1 ? ws + ws_o_bytes : nullptr), stream));
-  if ((rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 1, stream)) != SPD_OK) return rc;
-  if (ctx->kernel_timing) {
+  if (timing && (rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 1, stream)) != SPD_OK) return rc;
+  if (timing) {
     SPD_HIP(hipEventRecord(ds.ev_end, stream));
     ds.timed = true;
   }
+  return SPD_OK;
+}
+
+extern "C" int spd_decode_step(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* b) {
+  return decode_step_impl(ctx, pool, b, false);
+}
+
+extern "C" int spd_decode_step_noalloc(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch* b) {
+  return decode_step_impl(ctx, pool, b, true);
+}
+
+extern "C" int spd_noalloc_limits(uint64_t* metadata_bytes, uint64_t* workspace_bytes) {
+  if (metadata_bytes) *metadata_bytes = NOALLOC_STAGE_BYTES;
+  if (workspace_bytes) *workspace_bytes = NOALLOC_WS_BYTES;
   return SPD_OK;
 }
 

@@ -17,7 +17,7 @@ from typing import List, Optional, Sequence, Tuple
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("SEMIPD_LIB", os.path.join(_HERE, "libsemipd.so"))   # override: a differently built library
 
-SPD_OK, SPD_EINVAL, SPD_ENOMEM, SPD_ENOENT, SPD_EHIP, SPD_ESTATE = 0, -1, -2, -3, -5, -6
+SPD_OK, SPD_EINVAL, SPD_ENOMEM, SPD_ENOENT, SPD_EHIP, SPD_ESTATE, SPD_ETOOBIG = 0, -1, -2, -3, -5, -6, -7
 SPD_PHASE_PREFILL, SPD_PHASE_DECODE = 0, 1
 SPD_KV_GQA, SPD_KV_MLA_LATENT = 0, 1
 
@@ -31,6 +31,7 @@ EXPORTS = [
     "spd_decode_worker_start", "spd_decode_worker_stop", "spd_decode_worker_steps",
     "spd_ctrl_create", "spd_ctrl_destroy", "spd_ctrl_observe_ttft", "spd_ctrl_observe_tpot", "spd_ctrl_step", "spd_ctrl_model",
     "spd_rope_inv_freq", "spd_rope_qk", "spd_ffn_gate_up", "spd_ffn_pack_gate_up",
+    "spd_decode_step_noalloc", "spd_noalloc_limits",
 ]
 
 
@@ -100,6 +101,8 @@ def _load() -> C.CDLL:
         "spd_kv_gather": [vp, vp, C.c_int, u64, i32, vp, vp],
         "spd_prefill_step": [vp, vp, P(spd_prefill_batch)],
         "spd_decode_step": [vp, vp, P(spd_decode_batch)],
+        "spd_decode_step_noalloc": [vp, vp, P(spd_decode_batch)],
+        "spd_noalloc_limits": [P(u64), P(u64)],
         "spd_phase_sync": [vp, C.c_int],
         "spd_phase_query": [vp, C.c_int, P(C.c_int)],
         "spd_phase_wait_for": [vp, C.c_int, C.c_int],
@@ -308,6 +311,12 @@ def partition_masks(total_cus: int, granularity: int, prefill_cus: int, decode_c
     return list(pm), list(dm), p.value, d.value
 
 
+def noalloc_limits() -> Tuple[int, int]:
+    a, b = C.c_uint64(), C.c_uint64()
+    _check(lib.spd_noalloc_limits(C.byref(a), C.byref(b)), "spd_noalloc_limits")
+    return a.value, b.value
+
+
 def pool_bytes(kind: int, page_tokens: int, n_kv_heads: int, dim_k: int, dim_v: int, num_pages: int) -> int:
     desc = spd_pool_desc(kind, page_tokens, n_kv_heads, dim_k, dim_v, num_pages)
     out = C.c_uint64()
@@ -427,6 +436,9 @@ class Pool:
 
     def decode_step_batch(self, batch) -> None:
         _check(lib.spd_decode_step(self.ctx.h, self.h, C.byref(batch)), "spd_decode_step")
+
+    def decode_step_noalloc_batch(self, batch) -> None:
+        _check(lib.spd_decode_step_noalloc(self.ctx.h, self.h, C.byref(batch)), "spd_decode_step_noalloc")
 
     def decode_step(self, req_ids, ctx_lens, q, out, n_q_heads: int, scale: float, k_new=None, v_new=None, rope=None) -> None:
         self.decode_step_batch(self.make_decode_batch(req_ids, ctx_lens, q, out, n_q_heads, scale, k_new, v_new, rope))
