@@ -12,8 +12,10 @@ design notes):
     out = silu(g) * u     silu(z) = z / (1 + exp(-z))
 
 "One GEMM" means that both products come out of a single multiplication of x with the two weight
-matrices laid together; `pack_gate_up` is that joint matrix in the row order the library documents
-(blocks of 32 gate rows followed by the 32 up rows of the same output columns).
+matrices laid together; `joint_rows` is that joint matrix in the row order the library documents
+(blocks of 32 gate rows followed by the 32 up rows of the same output columns).  How the library
+stores that matrix in memory (its tiled byte layout) is not this module's business: the tests read
+it back with an inverse of their own, written from the header's index formula.
 
 Results are fp64 and NOT rounded: a comparison with a bf16 kernel allows for the output rounding.
 """
@@ -69,46 +71,3 @@ def gate_up_joint(x: np.ndarray, w_joint: np.ndarray) -> np.ndarray:
     for b in range(inter // PACK_BLOCK):
         out[:, 32 * b:32 * b + 32] = silu(y[:, 64 * b:64 * b + 32]) * y[:, 64 * b + 32:64 * b + 64]
     return out
-
-
-def pack_gate_up(w_gate: np.ndarray, w_up: np.ndarray) -> np.ndarray:
-    """The library's packed weight format, as a flat array of 2 inter * hidden elements (the layout is part of
-    the interface: it is written out in the header).  The joint matrix is cut into tiles of 256 joint rows x 32
-    hidden entries; tile (tn, ks) starts at element (tn * (hidden / 32) + ks) * 8192; inside a tile, joint row
-    256 tn + r keeps 64 bytes at element r * 32, and its 16-byte piece number s (8 elements) holds the hidden
-    entries 32 ks + 8 (s ^ ((r >> 2) & 3)) .. + 7.  inter a multiple of 128, hidden a multiple of 32."""
-    j = joint_rows(w_gate, w_up)
-    rows, hidden = j.shape
-    if rows % 256 or hidden % 32:
-        raise ValueError("inter must be a multiple of 128 and hidden a multiple of 32")
-    out = np.empty(rows * hidden, dtype=j.dtype)
-    n_ks = hidden // 32
-    for tn in range(rows // 256):
-        for ks in range(n_ks):
-            base = (tn * n_ks + ks) * 8192
-            for r in range(256):
-                for s_ in range(4):
-                    c = s_ ^ ((r >> 2) & 3)
-                    out[base + r * 32 + s_ * 8:base + r * 32 + s_ * 8 + 8] = j[256 * tn + r, 32 * ks + 8 * c:32 * ks + 8 * c + 8]
-    return out
-
-
-def unpack_gate_up(packed: np.ndarray, hidden: int):
-    """Inverse of pack_gate_up, written as the element-wise index formula: (w_gate, w_up)."""
-    packed = np.asarray(packed)
-    rows = packed.size // hidden
-    inter = rows // 2
-    n_ks = hidden // 32
-    w_gate = np.empty((inter, hidden), dtype=packed.dtype)
-    w_up = np.empty((inter, hidden), dtype=packed.dtype)
-    for R in range(rows):
-        tn, r = divmod(R, 256)
-        blk, jj = divmod(R, 64)
-        dst = w_gate if jj < 32 else w_up
-        n = 32 * blk + (jj & 31)
-        for k in range(hidden):
-            ks, kk = divmod(k, 32)
-            c, e = divmod(kk, 8)
-            s_ = c ^ ((r >> 2) & 3)
-            dst[n, k] = packed[(tn * n_ks + ks) * 8192 + r * 32 + s_ * 8 + e]
-    return w_gate, w_up

@@ -92,26 +92,24 @@ def test_joint_rows_and_single_product_give_the_same():
         F.joint_rows(wg[:40], wu[:40])
 
 
-def test_packed_format_places_elements_where_the_header_says():
-    # every element carries its own coordinates, so a misplaced one is seen at once
+def test_packed_weight_reader_follows_the_header_formula():
+    # the reader the GPU tests use for spd_ffn_pack_gate_up's output, on an array whose elements are their own
+    # flat positions: spots worked out by hand from the formula in include/semipd.h
+    import os
+    import sys
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    from ffn_layout import unpack_gate_up
     inter, hidden = 256, 96
-    wg = (np.arange(inter)[:, None] * 1000 + np.arange(hidden)[None, :]).astype(np.int64)
-    wu = wg + 500000
-    p = F.pack_gate_up(wg, wu)
-    assert p.shape == (2 * inter * hidden,)
-    assert sorted(p.tolist()) == sorted(wg.ravel().tolist() + wu.ravel().tolist())          # a permutation
+    packed = np.arange(2 * inter * hidden, dtype=np.int64)
+    g, u = unpack_gate_up(packed, hidden)
+    assert sorted(np.concatenate([g.ravel(), u.ravel()]).tolist()) == packed.tolist()           # a permutation
     n_ks = hidden // 32
-    # spot checks written out by hand: joint row 0 = gate row 0; its piece 0 holds hidden 0..7 (r >> 2 = 0)
-    np.testing.assert_array_equal(p[0:8], wg[0, 0:8])
-    # joint row 4 (gate row 4): (r >> 2) & 3 = 1, so piece 0 holds hidden 8..15 and piece 1 hidden 0..7
-    np.testing.assert_array_equal(p[4 * 32:4 * 32 + 8], wg[4, 8:16])
-    np.testing.assert_array_equal(p[4 * 32 + 8:4 * 32 + 16], wg[4, 0:8])
-    # joint row 32 is up row 0; tile (0, ks = 1) starts at element 8192
-    np.testing.assert_array_equal(p[8192 + 32 * 32:8192 + 32 * 32 + 8], wu[0, 32:40])
+    # joint row 0 = gate row 0, (r >> 2) & 3 = 0: piece s holds hidden 8 s ..
+    np.testing.assert_array_equal(g[0, 0:8], np.arange(0, 8))
+    # joint row 4 = gate row 4, (r >> 2) & 3 = 1: piece 0 holds hidden 8..15, piece 1 hidden 0..7
+    np.testing.assert_array_equal(g[4, 8:16], 4 * 32 + np.arange(0, 8))
+    np.testing.assert_array_equal(g[4, 0:8], 4 * 32 + 8 + np.arange(0, 8))
+    # joint row 32 = up row 0; hidden 32..39 lie in tile (0, ks = 1), which starts at element 8192
+    np.testing.assert_array_equal(u[0, 32:40], 8192 + 32 * 32 + np.arange(0, 8))
     # joint row 256 opens tile row tn = 1: gate row 128, at element (1 * n_ks + 0) * 8192
-    np.testing.assert_array_equal(p[n_ks * 8192:n_ks * 8192 + 8], wg[128, 0:8])
-    g2, u2 = F.unpack_gate_up(p, hidden)
-    np.testing.assert_array_equal(g2, wg)
-    np.testing.assert_array_equal(u2, wu)
-    with pytest.raises(ValueError):
-        F.pack_gate_up(wg[:64], wu[:64])
+    np.testing.assert_array_equal(g[128, 0:8], n_ks * 8192 + np.arange(0, 8))
