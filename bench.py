@@ -23,9 +23,24 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PRE, DEC = 0, 1
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated against a plain copy
-# kernel of known size (profiles/c2_hbm_traffic_pmc.md); keyed by workload, (prefill kernel, decode kernels)
-MEASURED_TRAFFIC = {"c2_llama3_8b": (100.9e6 + 67.1e6, 571.1e6 + 2.2e6)}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_pmc.md")
+
+
+def profiled_traffic(workload):
+    """HBM bytes per launch (prefill kernel, decode kernels) of `workload` as the hardware byte counters saw them.
+    Counters cannot be read from inside this process: rocprofv3 collects FETCH_SIZE and WRITE_SIZE in two runs of
+    this same command, and the summary of those runs holds one row per workload and phase,
+    `| traffic | <workload> | <phase> | <read bytes> | <written bytes> |` (calibrated against a plain copy of known
+    size).  Read from there, never typed in here; (None, None) where no such run has been summarised."""
+    got = {}
+    try:
+        for line in open(TRAFFIC_TABLE):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) == 5 and cells[0] == "traffic" and cells[1] == workload:
+                got[cells[2]] = float(cells[3]) + float(cells[4])
+    except OSError:
+        pass
+    return got.get("prefill"), got.get("decode")
 
 
 def parse():
@@ -37,6 +52,8 @@ def parse():
     ap.add_argument("--split", default="50/50", help="prefill%%/decode%% of the CUs for the headline run")
     ap.add_argument("--no-sweep", action="store_true", help="skip the CU-split sweep (solo + concurrent per split)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other single-GPU workloads (configs 3 and 4 at 50/50)")
+    ap.add_argument("--no-clock", action="store_true", help="skip the clock probe beside the phases")
     ap.add_argument("--pool-gb", type=float, default=None, help="override pool size (GB)")
     ap.add_argument("--no-scramble", action="store_true", help="experiment: hand out physical pages in order")
     ap.add_argument("--decode-per-prefill", type=int, default=0,
@@ -158,20 +175,53 @@ class Bench:
         self.prefill(); self.decode(); self.sync()          # both phases adopt the new streams
         return self.ctx.get_partition()[:2]
 
-    def copy_ceiling(self, phase, nbytes=1 << 30, reps=3):
-        """GB/s (read + write bytes) of a plain copy kernel on the phase's stream: streaming ceiling of its CU share"""
+    def read_ceiling(self, phase, nbytes=4 << 30, reps=6):
+        """GB/s of a read-only streaming kernel (eight 16-byte loads in flight per lane, nothing written) over
+        `nbytes` on the phase's stream, the other phase idle: what the phase's CU share can read out of HBM at
+        best, the yardstick of the decode kernels."""
         torch = self.torch
-        if not hasattr(self, "_cp"):
-            self._cp = (torch.empty(nbytes, dtype=torch.uint8, device=self.dev),
-                        torch.empty(nbytes, dtype=torch.uint8, device=self.dev))
-        a, b = self._cp
-        self.ctx.phase_copy(phase, b, a, nbytes)
+        if not hasattr(self, "_rd"):
+            self._rd = torch.empty(nbytes // 8, dtype=torch.int64, device=self.dev).random_()
+        self.ctx.phase_read(phase, self._rd, nbytes)
         self.ctx.phase_sync(phase)
         t0 = time.perf_counter()
         for _ in range(reps):
-            self.ctx.phase_copy(phase, b, a, nbytes)
+            self.ctx.phase_read(phase, self._rd, nbytes)
         self.ctx.phase_sync(phase)
-        return 2.0 * nbytes * reps / (time.perf_counter() - t0) / 1e9
+        return nbytes * reps / (time.perf_counter() - t0) / 1e9
+
+    def clock_probe(self, load, ms=4.0):
+        """The shader clock the chip holds under `load` ("idle", "prefill", "decode", "both"): one wave on a
+        stream of its own runs a fixed chain of dependent adds for about `ms` milliseconds while the load runs;
+        returns MHz (cycle-counter ticks per tick of the constant 100 MHz counter) and cycles per add."""
+        torch = self.torch
+        if not hasattr(self, "_clk"):
+            self._clk = (torch.cuda.Stream(device=self.dev), torch.zeros(4, dtype=torch.int64, device=self.dev))
+        side, buf = self._clk
+        iters = int(ms * 1e-3 * 2.0e9 / (64 * 5))          # ~5 cycles per dependent add
+        self.sync()
+        torch.cuda.synchronize()
+        worker = None
+        if load == "both":
+            worker = self.pool.decode_worker_start(self.dec_batches)
+            for _ in range(3):
+                self.prefill()
+            self.ctx.phase_sync(PRE)
+        t_end = time.perf_counter() + ms * 1.5e-3
+        self.ctx.clock_probe(side.cuda_stream, iters, buf)
+        while time.perf_counter() < t_end:
+            if load in ("prefill", "both"):
+                self.prefill()
+            elif load == "decode":
+                self.decode()
+            else:
+                time.sleep(0.0002)
+        if worker is not None:
+            self.pool.decode_worker_stop(worker)
+        self.sync()
+        side.synchronize()
+        w, c, _, _ = (int(x) for x in buf.cpu().tolist())
+        return {"mhz": 100.0 * c / max(w, 1), "cycles_per_add": c / (64.0 * iters), "probe_ms": w / 1e5}
 
     def time_solo(self, phase, n):
         """median kernel-level and step-level ms of `n` back-to-back steps of one phase, other phase idle"""
@@ -304,19 +354,15 @@ def cpu_baseline(cfg, r):
             "prefill_tok_s": sum(cfg.prefill_lens) / t_p, "decode_tok_s": len(cfg.decode_ctx) / t_d}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (the hot path of one MI355X; --gpus must be 1)", file=sys.stderr)
-        sys.exit(2)
-    import workloads as W
-    cfg = W.get_config(args.config)
+def measure_config(cfg, args, steps, warmup, sweep, clock):
+    """All figures of one workload: the headline split (solo passes, then the two asynchronous workers), optionally
+    the split sweep and the clock probe; returns the workload's part of the JSON line."""
     bench = Bench(cfg, args.pool_gb, not args.no_scramble)
     p_pct, d_pct = (int(x) for x in args.split.split("/"))
 
     def measure_split(pp, dp, steps, warmup, only=None):
         p_cus, d_cus = bench.set_split(pp, dp)
-        copy_gbs = bench.copy_ceiling(DEC)
+        read_gbs = bench.read_ceiling(DEC)
         if args.decode_per_prefill > 0 or only:
             # fixed mix in lockstep (profiling aid), or one phase alone
             r = max(1, args.decode_per_prefill)
@@ -331,61 +377,104 @@ def main():
             wall_ms, n_dec, _, _ = run_async(bench, steps)                              # the timed region: K prefill steps, decode free-running
             r = n_dec / steps
             _, _, pk, dk = run_async(bench, min(steps, 64), timing=True)               # again, kernels bracketed by events
+        dec_gbs = bench.decode_bytes / (median(dk) * 1e-3) / 1e9 if dk else None
+        solo_dec_gbs = bench.decode_bytes / (solo_d_k * 1e-3) / 1e9
         return {"split": f"{pp}/{dp}", "prefill_cus": p_cus, "decode_cus": d_cus, "decode_per_prefill": r,
-                "ms_per_step": wall_ms, "decode_share_copy_gbs": copy_gbs,
+                "ms_per_step": wall_ms, "decode_share_read_gbs": read_gbs,
                 "prefill_tok_s": bench.T / wall_ms * 1e3 if only != "decode" else 0.0,
                 "decode_tok_s": r * bench.B / wall_ms * 1e3 if only != "prefill" else 0.0,
                 "prefill_kernel_ms": median(pk), "decode_kernel_ms": median(dk),
                 "prefill_tflops": bench.prefill_flops / (median(pk) * 1e-3) / 1e12 if pk else None,
-                "decode_gbs": bench.decode_bytes / (median(dk) * 1e-3) / 1e9 if dk else None,
+                "decode_gbs": dec_gbs, "decode_frac_of_share_read": dec_gbs / read_gbs if dec_gbs else None,
                 "solo": {"prefill_kernel_ms": solo_p_k, "prefill_step_ms": solo_p_w, "decode_kernel_ms": solo_d_k,
                          "decode_step_ms": solo_d_w,
                          "prefill_tflops": bench.prefill_flops / (solo_p_k * 1e-3) / 1e12,
-                         "decode_gbs": bench.decode_bytes / (solo_d_k * 1e-3) / 1e9}}
+                         "decode_gbs": solo_dec_gbs, "decode_frac_of_share_read": solo_dec_gbs / read_gbs}}
 
-    head = measure_split(p_pct, d_pct, args.steps, args.warmup, args.only)
+    head = measure_split(p_pct, d_pct, steps, warmup, args.only)
     splits = [head]
-    if not args.no_sweep:
+    if sweep:
         for pp, dp in list(cfg.cu_splits) + [(100, 100)]:
             if (pp, dp) != (p_pct, d_pct):
-                splits.append(measure_split(pp, dp, max(10, args.steps // 2), 2))
+                splits.append(measure_split(pp, dp, max(10, steps // 2), 2))
+    clocks = None
+    if clock:
+        bench.set_split(p_pct, d_pct)
+        clocks = {load: bench.clock_probe(load) for load in ("idle", "prefill", "decode", "both")}
 
     r = head["decode_per_prefill"]
     tokens_per_step = (bench.T if args.only != "decode" else 0) + (r * bench.B if args.only != "prefill" else 0)
-    pre_ms = head["prefill_kernel_ms"]
-    result = {
-        "metric": "prefill tok/s + decode tok/s at CU split; % MFMA peak / % HBM BW",
+    traffic_p, traffic_d = profiled_traffic(cfg.name)
+    L = cfg.layer
+    part = {
         "value": tokens_per_step / head["ms_per_step"] * 1e3,
-        "unit": "tokens/s (prefill + decode tokens, one attention layer)",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "ms_per_step": head["ms_per_step"],
         "config": {"workload": cfg.name, "note": cfg.note, "prefill_batch": list(cfg.prefill_lens),
                    "decode_batch": bench.B, "decode_ctx_mean": sum(cfg.decode_ctx) / bench.B,
-                   "q_heads": cfg.layer.n_q_heads, "kv_heads": cfg.layer.n_kv_heads, "head_dim": cfg.layer.dim_qk,
-                   "page_tokens": cfg.layer.page_tokens, "pool_pages": bench.num_pages,
+                   "q_heads": L.n_q_heads, "kv_heads": L.n_kv_heads, "head_dim": L.dim_qk,
+                   "page_tokens": L.page_tokens, "pool_pages": bench.num_pages,
                    "cu_split": head["split"], "prefill_cus": head["prefill_cus"], "decode_cus": head["decode_cus"],
                    "step": (f"1 prefill step || {r} decode steps (lockstep)" if isinstance(r, int) else
                             f"1 prefill step, the decode worker free-running beside it ({r:.2f} decode steps per prefill step)"),
                    "only": args.only},
         "prefill_tok_s": head["prefill_tok_s"], "decode_tok_s": head["decode_tok_s"],
-        "roofline": {"bound": "mfma", "kernel": f"prefill_kernel<{cfg.layer.dim_qk},{cfg.layer.dim_v}>", "achieved": head["prefill_tflops"],
+        "roofline": {"bound": "mfma", "kernel": f"prefill_kernel<{L.dim_qk},{L.dim_v}>", "achieved": head["prefill_tflops"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": (head["prefill_tflops"] or 0.0) / PEAK_BF16_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC.get(cfg.name, (None, None))[0],
-                     "kernel_ms": pre_ms, "flops_per_launch": bench.prefill_flops,
+                     "traffic": traffic_p, "traffic_source": "profiles/hbm_traffic_pmc.md" if traffic_p else None,
+                     "kernel_ms": head["prefill_kernel_ms"], "flops_per_launch": bench.prefill_flops,
                      "share_cus": head["prefill_cus"],
                      "frac_of_share_peak": (head["prefill_tflops"] or 0.0) / (PEAK_BF16_TFLOPS * head["prefill_cus"] / bench.total_cus)},
-        "roofline_decode": {"bound": "hbm", "kernel": ("decode_mla_kernel" if cfg.layer.kind == "mla" else f"decode_gqa_kernel<{cfg.layer.dim_qk}>") + " (+combine)", "achieved": head["decode_gbs"],
+        "roofline_decode": {"bound": "hbm", "kernel": ("decode_mla_kernel" if L.kind == "mla" else f"decode_gqa_kernel<{L.dim_qk}>") + " (+combine)", "achieved": head["decode_gbs"],
                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": (head["decode_gbs"] or 0.0) / PEAK_HBM_GBS,
-                            "traffic": MEASURED_TRAFFIC.get(cfg.name, (None, None))[1], "kernel_ms": head["decode_kernel_ms"],
-                            "bytes_per_launch": bench.decode_bytes, "share_cus": head["decode_cus"]},
+                            "traffic": traffic_d, "traffic_source": "profiles/hbm_traffic_pmc.md" if traffic_d else None,
+                            "kernel_ms": head["decode_kernel_ms"],
+                            "bytes_per_launch": bench.decode_bytes, "share_cus": head["decode_cus"],
+                            "share_read_ceiling_gbs": head["decode_share_read_gbs"],
+                            "frac_of_share_read_ceiling": head["decode_frac_of_share_read"],
+                            "solo_frac_of_share_read_ceiling": head["solo"]["decode_frac_of_share_read"]},
         "splits": splits,
     }
+    if clocks:
+        part["clock_probe"] = clocks
+    bench.close()
+    del bench
+    gc.collect()
+    return part, r
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the hot path of one MI355X; --gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import workloads as W
+    cfg = W.get_config(args.config)
+    part, r = measure_config(cfg, args, args.steps, args.warmup, not args.no_sweep, not args.no_clock)
+    result = {
+        "metric": "prefill tok/s + decode tok/s at CU split; % MFMA peak / % HBM BW",
+        "value": part.pop("value"),
+        "unit": "tokens/s (prefill + decode tokens, one attention layer)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": part.pop("ms_per_step"),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+    }
+    result.update(part)
+    if not args.no_extra and args.only is None:
+        # the other workloads that fit one GPU, each with rooflines of its own, at the headline split
+        result["configs"] = {}
+        for name in ("c3", "c4"):
+            other = W.get_config(name)
+            if other.name == cfg.name:
+                continue
+            steps = max(10, args.steps // 2)
+            sub, _ = measure_config(other, args, steps, 2, False, False)
+            sub["steps"] = steps
+            sub["unit"] = result["unit"]
+            result["configs"][other.name] = sub
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cfg, r)
     print(json.dumps(result))
     sys.stdout.flush()
-    bench.close()
 
 
 if __name__ == "__main__":

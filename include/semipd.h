@@ -10,7 +10,13 @@
  *
  * Conventions
  *  - Every call returns an int status (SPD_OK or a negative SPD_E*), never throws,
- *    and leaves all library state unchanged when it fails.
+ *    and leaves all library state unchanged when it fails: pool, block tables, operation
+ *    numbers, and the partition (a step adopts a staged partition only once nothing but a
+ *    HIP call can still fail).  SPD_EHIP is the exception: a failing HIP call may leave
+ *    work of the step enqueued and its reservations made.
+ *  - Every device tensor handed to a step (q, k, v, latent, out, k_new, v_new, the dense side
+ *    of spd_kv_write / spd_kv_gather) must start on a 16-byte boundary: the kernels move 16
+ *    bytes per lane.  SPD_EINVAL otherwise.
  *  - "device" pointers are HIP device addresses owned by the caller (the library
  *    never frees them); "host" pointers are ordinary host memory read during the
  *    call only.  Tensors are dense row-major bf16 unless stated otherwise.
@@ -100,6 +106,13 @@ int spd_pool_stats(spd_pool* pool, int64_t* total, int64_t* free_pages, int64_t*
  * block table to ceil(n_tokens_total / P) blocks (creating the request if new; never shrinks);
  * all-or-nothing: SPD_ENOMEM and no change if too few blocks are free.  free returns every
  * block of the request, pushed back last-to-first, and forgets the request.
+ * Lifetime rule of free: the blocks can be handed out again by the very next reserve, on either
+ * worker, so a request may be freed only after every step that was given its id (prefill step,
+ * decode step, spd_kv_write, spd_kv_gather; the decode worker's steps too) has finished on the
+ * GPU - after spd_phase_sync, or spd_phase_query reporting done, of the phases that used it.
+ * The library checks it: while such a step may still be running, free returns SPD_ESTATE and
+ * changes nothing (it never waits).  Work the caller enqueues itself on a phase's stream is
+ * the caller's to order.
  * op_seq_out (nullable) receives the operation's position (1, 2, ...) in the pool's
  * linearised order of successful mutating calls; failed calls consume no number. */
 int spd_kv_reserve(spd_pool* pool, uint64_t req_id, int32_t n_tokens_total, uint64_t* op_seq_out);
@@ -317,31 +330,6 @@ int spd_phase_query(spd_ctx* ctx, int phase, int* done);
 int spd_phase_wait_for(spd_ctx* ctx, int phase, int other);
 /* The phase's current hipStream_t, for callers that enqueue their own work or events. */
 int spd_phase_stream(spd_ctx* ctx, int phase, void** hip_stream_out);
-/* GPU time of the phase's most recent step in milliseconds (waits for that step).  Steps are
- * timed only while timing is on (spd_set_kernel_timing); otherwise SPD_ESTATE. */
-int spd_phase_last_ms(spd_ctx* ctx, int phase, float* ms);
-
-/* Two environment variables, read at every step, override choices the library otherwise makes
- * itself; they exist for measurements and change no result:
- *   SPD_PREFILL_PERSISTENT=0|1  launch the prefill kernel with one workgroup per work item (0) or
- *                               with one persistent workgroup per compute unit (1) regardless of
- *                               the partition;
- *   SPD_DECODE_CHUNK_TILES=n    fix the split-K chunk of the decode kernels to n 16-token tiles. */
-
-/* Measurement aid.  With timing on, each step is bracketed by HIP events (spd_phase_last_ms)
- * and, separately, so are its attention kernel(s) (not the
- * block-table upload or the page write) with HIP events on the phase's stream; the last
- * 256 steps are kept.  spd_phase_kernel_ms waits for the phase, writes the durations
- * (milliseconds, oldest first) of the steps recorded since the last call to host out[cap]
- * and their number to *n_out.  Off by default (each record costs a few microseconds). */
-int spd_set_kernel_timing(spd_ctx* ctx, int on);
-int spd_phase_kernel_ms(spd_ctx* ctx, int phase, float* out, int32_t cap, int32_t* n_out);
-
-/* Measurement aid: a plain device-to-device copy kernel (16 bytes per lane, grid-stride) of
- * `bytes` (a multiple of 16) from src to dst on the phase's current stream.  Its known traffic
- * calibrates hardware byte counters, and its speed on a masked stream is the streaming ceiling
- * of that CU share. */
-int spd_phase_copy(spd_ctx* ctx, int phase, void* dst, const void* src, uint64_t bytes);
 
 /* ------------------------------------------------------------------ partition
  * Paper, "Computational Resource Controller": a configuration (x, y) gives x % of the
@@ -368,11 +356,6 @@ int spd_phase_cu_mask(spd_ctx* ctx, int phase, uint32_t* words, int32_t cap, int
  * prefill_words / decode_words and the rounded counts to *p_out / *d_out. */
 int spd_partition_masks(int total_cus, int granularity, int prefill_cus, int decode_cus,
                         uint32_t* prefill_words, uint32_t* decode_words, int* p_out, int* d_out);
-
-/* Debug aid: run a tiny kernel of `n_blocks` workgroups on the phase's current stream and
- * report, to host ids[cap], the distinct hardware (XCD << 16 | SE << 8 | CU) ids that ran
- * them; used to check that a masked stream stays on its CUs. */
-int spd_phase_probe_cus(spd_ctx* ctx, int phase, int32_t n_blocks, int32_t* ids, int32_t cap, int32_t* n_ids);
 
 /* ------------------------------------------------------------- SLO-aware partition adjuster
  * Paper, "Dynamic Adjusting Method": Algorithm 1 (SLO-aware adjusting algorithm) with the
@@ -415,6 +398,57 @@ int spd_ctrl_step(spd_ctrl* c, int64_t iter, int32_t x0, int32_t y0, int32_t* x,
 /* The current model to host out[5] = {a1, lambda, b1, a2, b2} (zeros before the first window). */
 int spd_ctrl_model(spd_ctrl* c, double* out);
 
+/* ===================================================================================
+ * MEASUREMENT AND DEBUG AIDS.  Nothing below is part of the hot path's interface: no step
+ * needs these calls, they change no result, and a serving loop never makes them.  They are
+ * exported for the benchmark, the profiles and the tests of the partition.
+ * =================================================================================== */
+
+/* Two environment variables, read once by spd_ctx_create (never by a step), override choices
+ * the library otherwise makes itself:
+ *   SPD_PREFILL_PERSISTENT=0|1  launch the prefill kernel with one workgroup per work item (0) or
+ *                               with one persistent workgroup per compute unit (1) regardless of
+ *                               the partition;
+ *   SPD_DECODE_CHUNK_TILES=n    fix the split-K chunk of the decode kernels to n 16-token tiles. */
+
+/* With timing on, each step is bracketed by HIP events (spd_phase_last_ms)
+ * and, separately, so are its attention kernel(s) (not the
+ * block-table upload or the page write) with HIP events on the phase's stream; the last
+ * 256 steps are kept.  spd_phase_kernel_ms waits for the phase, writes the durations
+ * (milliseconds, oldest first) of the steps recorded since the last call to host out[cap]
+ * and their number to *n_out.  Off by default (each record costs a few microseconds). */
+int spd_set_kernel_timing(spd_ctx* ctx, int on);
+int spd_phase_kernel_ms(spd_ctx* ctx, int phase, float* out, int32_t cap, int32_t* n_out);
+/* GPU time of the phase's most recent step in milliseconds (waits for that step).  Steps are
+ * timed only while timing is on (spd_set_kernel_timing); otherwise SPD_ESTATE. */
+int spd_phase_last_ms(spd_ctx* ctx, int phase, float* ms);
+
+/* A plain device-to-device copy kernel (16 bytes per lane, grid-stride) of `bytes` (a
+ * multiple of 16; src, dst 16-byte aligned) from src to dst on the phase's current stream.
+ * Its known traffic calibrates hardware byte counters. */
+int spd_phase_copy(spd_ctx* ctx, int phase, void* dst, const void* src, uint64_t bytes);
+
+/* A read-only streaming kernel over `bytes` (a multiple of 16) of device memory at src
+ * (16-byte aligned) on the phase's current stream: eight independent 16-byte loads in flight
+ * per lane, nothing written.  Its speed on a masked stream is the read ceiling of that CU
+ * share, the yardstick for the decode kernels (which read every cached byte once and write
+ * almost nothing). */
+int spd_phase_read(spd_ctx* ctx, int phase, const void* src, uint64_t bytes);
+
+/* One wave, on the caller's stream `hip_stream` (a hipStream_t; null: the default stream), runs
+ * 64 * iters dependent integer adds and writes to device dev_out[3] (8-byte aligned): the time
+ * that took in ticks of the constant 100 MHz counter, in ticks of the shader cycle counter,
+ * and the chain's result.  Run beside the two phases it shows the clock the chip holds under
+ * that load (cycle ticks / constant ticks x 100 MHz).  1 <= iters <= 2^32. */
+int spd_clock_probe(spd_ctx* ctx, void* hip_stream, uint64_t iters, uint64_t* dev_out);
+
+/* Run a tiny kernel of `n_blocks` workgroups on the phase's current stream and
+ * report, to host ids[cap], the distinct hardware (XCD << 16 | SE << 8 | CU) ids that ran
+ * them; used to check that a masked stream stays on its CUs. */
+int spd_phase_probe_cus(spd_ctx* ctx, int phase, int32_t n_blocks, int32_t* ids, int32_t cap, int32_t* n_ids);
+
+
+/* ------------------------------------------------------------------ errors */
 const char* spd_strerror(int status);
 /* The hipError_t of the most recent SPD_EHIP on this thread (0 if none). */
 int spd_last_hip_error(void);

@@ -65,6 +65,9 @@ extern "C" int spd_ctx_create(int device, spd_ctx** out) {
   spd_ctx* c = new (std::nothrow) spd_ctx();
   if (!c) return SPD_EINVAL;
   c->device = device;
+  // the two measurement overrides are read here, once: the steps never touch the environment
+  if (const char* env = getenv("SPD_PREFILL_PERSISTENT")) c->env_prefill_persistent = atoi(env) != 0;
+  if (const char* env = getenv("SPD_DECODE_CHUNK_TILES")) c->env_decode_chunk_tiles = std::max(0, atoi(env));
   if (device >= 0) {
     hipDeviceProp_t prop;
     hipError_t e = hipGetDeviceProperties(&prop, device);
@@ -220,6 +223,12 @@ int phase_enter(spd_ctx* ctx, int phase, hipStream_t* stream_out) {
   return SPD_OK;
 }
 
+static void raise_done_seq(spd_phase_state& s, uint64_t seq) {
+  uint64_t cur = s.done_seq.load(std::memory_order_relaxed);
+  while (cur < seq && !s.done_seq.compare_exchange_weak(cur, seq, std::memory_order_release)) {
+  }
+}
+
 int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out, bool may_alloc) {
   spd_phase_state& s = ctx->phase[phase];
   spd_stage& st = s.ring[s.ring_pos];
@@ -230,6 +239,7 @@ int stage_acquire(spd_ctx* ctx, int phase, size_t bytes, spd_stage** out, bool m
     while ((e = hipEventQuery(st.done)) == hipErrorNotReady) std::this_thread::sleep_for(std::chrono::microseconds(20));
     if (e != hipSuccess) return hip_fail(e);
     st.in_flight = false;
+    raise_done_seq(s, st.seq.load(std::memory_order_relaxed));
   }
   if (!may_alloc && (!st.done || st.cap < bytes || !st.dev_static)) return SPD_ETOOBIG;
   if (!st.done) SPD_HIP(hipEventCreateWithFlags(&st.done, hipEventDisableTiming));
@@ -253,21 +263,49 @@ int stage_host_as_device(spd_stage* st, void** out) {
   return SPD_OK;
 }
 
-int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream, bool copy, char* dev) {
-  spd_phase_state& s = ctx->phase[phase];
+int stage_copy(spd_stage* st, size_t bytes, hipStream_t stream, char* dev) {
   // The step's metadata crosses to the device with a small copy kernel on the phase's own stream
   // (pinned host memory is device-readable).  hipMemcpyAsync would put it on a copy path that the
   // two phases share: with each phase driven by its own thread the copies then wait for each
   // other's predecessors and one phase starves the other.
+  void* host_dev = nullptr;
+  SPD_HIP(hipHostGetDevicePointer(&host_dev, st->host, 0));
+  SPD_HIP(launch_copy(dev ? dev : st->dev, host_dev, (bytes + 15) & ~(size_t)15, 1, stream));
+  return SPD_OK;
+}
+
+// Called behind the step's last kernel: the slot's event then also says that the step has finished, which is
+// what spd_kv_free asks about.
+int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream, bool copy, char* dev) {
+  spd_phase_state& s = ctx->phase[phase];
   if (copy) {
-    void* host_dev = nullptr;
-    SPD_HIP(hipHostGetDevicePointer(&host_dev, st->host, 0));
-    SPD_HIP(launch_copy(dev ? dev : st->dev, host_dev, (bytes + 15) & ~(size_t)15, 1, stream));
+    int rc = stage_copy(st, bytes, stream, dev);
+    if (rc != SPD_OK) return rc;
   }
   SPD_HIP(hipEventRecord(st->done, stream));
+  st->seq.store(s.issue_seq.load(std::memory_order_relaxed) + 1, std::memory_order_release);   // after the record
+  s.issue_seq.fetch_add(1, std::memory_order_release);
   st->in_flight = true;
   s.ring_pos = (s.ring_pos + 1) % 4;
   return SPD_OK;
+}
+
+bool phase_step_done(spd_ctx* ctx, int phase, uint64_t seq) {
+  if (seq == 0 || ctx->device < 0) return true;
+  spd_phase_state& s = ctx->phase[phase];
+  if (s.done_seq.load(std::memory_order_acquire) >= seq) return true;
+  (void)hipSetDevice(ctx->device);
+  // A slot whose number is `seq` or later carries an event recorded behind that step's last kernel (the number is
+  // stored after the record, so reading it first means the event is at least that recent).
+  for (spd_stage& st : s.ring) {
+    const uint64_t q = st.seq.load(std::memory_order_acquire);
+    if (q >= seq && st.done && hipEventQuery(st.done) == hipSuccess) {
+      raise_done_seq(s, q);
+      return true;
+    }
+  }
+  (void)hipGetLastError();      // hipErrorNotReady is not an error to keep
+  return false;
 }
 
 int workspace_reserve(spd_ctx* ctx, int phase, size_t bytes, char** out) {
@@ -330,7 +368,9 @@ extern "C" int spd_phase_sync(spd_ctx* ctx, int phase) {
   if (ctx->device < 0) return SPD_ESTATE;
   hipStream_t s;
   { std::lock_guard<std::mutex> lk(ctx->part_mu); s = ctx->phase[phase].stream; }
+  const uint64_t issued = ctx->phase[phase].issue_seq.load(std::memory_order_acquire);
   SPD_HIP(hipStreamSynchronize(s));
+  raise_done_seq(ctx->phase[phase], issued);
   return SPD_OK;
 }
 
@@ -339,8 +379,9 @@ extern "C" int spd_phase_query(spd_ctx* ctx, int phase, int* done) {
   if (ctx->device < 0) return SPD_ESTATE;
   hipStream_t s;
   { std::lock_guard<std::mutex> lk(ctx->part_mu); s = ctx->phase[phase].stream; }
+  const uint64_t issued = ctx->phase[phase].issue_seq.load(std::memory_order_acquire);
   hipError_t e = hipStreamQuery(s);
-  if (e == hipSuccess) { *done = 1; return SPD_OK; }
+  if (e == hipSuccess) { raise_done_seq(ctx->phase[phase], issued); *done = 1; return SPD_OK; }
   if (e == hipErrorNotReady) { *done = 0; return SPD_OK; }
   return hip_fail(e);
 }
@@ -378,6 +419,25 @@ extern "C" int spd_phase_copy(spd_ctx* ctx, int phase, void* dst, const void* sr
   int rc = phase_enter(ctx, phase, &stream);
   if (rc != SPD_OK) return rc;
   SPD_HIP(launch_copy(dst, src, bytes, ctx->phase[phase].active_cus, stream));
+  return SPD_OK;
+}
+
+extern "C" int spd_phase_read(spd_ctx* ctx, int phase, const void* src, uint64_t bytes) {
+  if (!ctx || phase < 0 || phase > 1 || !src || bytes == 0 || bytes % 16 != 0) return SPD_EINVAL;
+  if ((uintptr_t)src & 15) return SPD_EINVAL;
+  hipStream_t stream;
+  int rc = phase_enter(ctx, phase, &stream);
+  if (rc != SPD_OK) return rc;
+  SPD_HIP(launch_read(src, bytes, ctx->phase[phase].active_cus, nullptr, stream));
+  return SPD_OK;
+}
+
+extern "C" int spd_clock_probe(spd_ctx* ctx, void* hip_stream, uint64_t iters, uint64_t* dev_out) {
+  if (!ctx || !dev_out || iters == 0 || iters > (1ull << 32)) return SPD_EINVAL;
+  if ((uintptr_t)dev_out & 7) return SPD_EINVAL;
+  if (ctx->device < 0) return SPD_ESTATE;
+  SPD_HIP(hipSetDevice(ctx->device));
+  SPD_HIP(launch_clock_probe(iters, dev_out, (hipStream_t)hip_stream));
   return SPD_OK;
 }
 

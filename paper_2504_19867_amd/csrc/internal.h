@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include <map>
+#include <atomic>
 #include <mutex>
 #include <unordered_map>
 #include <vector>
@@ -93,6 +94,12 @@ inline int hip_fail(hipError_t e) { g_last_hip_error = (int)e; return SPD_EHIP; 
 }  // namespace spd
 
 // ------------------------------------------------------------------------------------------ objects
+// A request's block table, and for each phase the number of the last step of that phase that took the table
+// (0: none): spd_kv_free refuses while such a step may still be running on the GPU.
+struct spd_req_table : std::vector<int32_t> {
+  uint64_t last_use[2] = {0, 0};
+};
+
 struct spd_pool {
   spd_ctx* ctx;
   spd_pool_desc desc;
@@ -103,7 +110,7 @@ struct spd_pool {
   std::vector<int32_t> free_stack;                // top = back()
   int64_t used = 0;
   uint64_t op_seq = 0;
-  std::unordered_map<uint64_t, std::vector<int32_t>> tables;
+  std::unordered_map<uint64_t, spd_req_table> tables;
 };
 
 struct spd_stage {          // pinned host buffer + device twin, reused round-robin per phase
@@ -111,8 +118,9 @@ struct spd_stage {          // pinned host buffer + device twin, reused round-ro
   char* dev = nullptr;
   size_t cap = 0;
   char* dev_static = nullptr;   // this slot's metadata twin inside the static scratch array (decode phase)
-  hipEvent_t done = nullptr;
+  hipEvent_t done = nullptr;          // recorded behind the last kernel of the step that used the slot
   bool in_flight = false;
+  std::atomic<uint64_t> seq{0};       // number of that step (stored after the event has been recorded)
 };
 
 struct spd_phase_state {
@@ -124,6 +132,8 @@ struct spd_phase_state {
   std::vector<uint32_t> active_mask, pending_mask;
   spd_stage ring[4];
   int ring_pos = 0;
+  std::atomic<uint64_t> issue_seq{0};  // steps (ring commits) of this phase so far; the next step's number is this + 1
+  std::atomic<uint64_t> done_seq{0};   // a step number known to have finished on the GPU (steps of a phase finish in order)
   hipEvent_t ev_start = nullptr, ev_end = nullptr, ev_switch = nullptr, ev_cross = nullptr;
   bool timed = false;
   char* workspace = nullptr;           // split-K partials (decode)
@@ -142,6 +152,8 @@ struct spd_ctx {
   std::map<std::vector<uint32_t>, hipStream_t> stream_cache;
   spd_phase_state phase[2];
   bool kernel_timing = false;
+  int env_prefill_persistent = -1;     // SPD_PREFILL_PERSISTENT as read by spd_ctx_create (-1: not set)
+  int env_decode_chunk_tiles = 0;      // SPD_DECODE_CHUNK_TILES as read by spd_ctx_create (0: not set)
   char* scratch = nullptr;             // this device's copy of the static scratch array (noalloc.hip)
 };
 
@@ -156,6 +168,9 @@ int scratch_resolve(int device, char** out);   // noalloc.hip: address of `devic
 int stage_commit(spd_ctx* ctx, int phase, spd_stage* st, size_t bytes, hipStream_t stream, bool copy = true,
                  char* dev = nullptr);
 int stage_host_as_device(spd_stage* st, void** out);   // device-readable address of the pinned host buffer
+int stage_copy(spd_stage* st, size_t bytes, hipStream_t stream, char* dev = nullptr);   // host buffer -> device twin
+// true if step number `seq` of `phase` has finished on the GPU (any thread may ask)
+bool phase_step_done(spd_ctx* ctx, int phase, uint64_t seq);
 int workspace_reserve(spd_ctx* ctx, int phase, size_t bytes, char** out);
 int kernel_timing_mark(spd_ctx* ctx, int phase, int which, hipStream_t stream);   // which: 0 begin, 1 end
 // rope.cpp: SPD_OK if the configuration is well-formed; the frequency table (rotary_dim / 2 doubles)
@@ -197,6 +212,8 @@ hipError_t launch_rope_append(const PoolGeom& g, char* pool_base, const TileDesc
                               int off, bool interleaved, const double* d_w, hipStream_t stream);
 hipError_t launch_probe(int32_t* d_ids, int n_blocks, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, int cus, hipStream_t stream);
+hipError_t launch_read(const void* src, uint64_t bytes, int cus, uint32_t* sink, hipStream_t stream);
+hipError_t launch_clock_probe(uint64_t iters, uint64_t* d_out, hipStream_t stream);
 bool prefill_shape_supported(int dqk, int dv);
 int prefill_heads_per_block(int group);   // query heads of one KV head that share a workgroup
 int prefill_block_m(int group);           // query rows per workgroup

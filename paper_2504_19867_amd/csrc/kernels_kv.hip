@@ -254,6 +254,58 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, cons
   for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Read-only stream: every lane keeps eight independent 16-byte loads in flight, grid-stride over n16 pieces; what is
+// read is folded into one word that is stored only if it equals a value it cannot practically take, so the loads stay
+// and nothing is written.
+__global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src, uint64_t n16, uint32_t* __restrict__ sink) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  uint32_t acc = 0;
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    uint4 r[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = load_once(src + i + j * stride);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc ^= r[j].x ^ r[j].y ^ r[j].z ^ r[j].w;
+  }
+  for (; i < n16; i += stride) {
+    const uint4 r = load_once(src + i);
+    acc ^= r.x ^ r.y ^ r.z ^ r.w;
+  }
+  if (acc == 0x9e3779b9u && sink) sink[0] = acc;
+}
+
+hipError_t launch_read(const void* src, uint64_t bytes, int cus, uint32_t* sink, hipStream_t stream) {
+  hipLaunchKernelGGL(read_kernel, dim3((unsigned)cus * 8), dim3(256), 0, stream, (const uint4*)src, bytes / 16, sink);
+  return hipGetLastError();
+}
+
+// One wave runs a chain of `iters` dependent integer adds (each waits for the one before: a fixed number of shader
+// clock cycles whatever else the chip is doing) and reports how long that took on the constant-rate 100 MHz counter
+// and on the shader cycle counter.  out[0] = constant-rate ticks, out[1] = cycle-counter ticks, out[2] = the chain's
+// result (keeps it alive).
+__global__ __launch_bounds__(64) void clock_probe_kernel(uint64_t iters, uint64_t* __restrict__ out) {
+  uint32_t x = (uint32_t)threadIdx.x;
+  const uint64_t w0 = wall_clock64();
+  const uint64_t c0 = __builtin_readcyclecounter();
+  for (uint64_t i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int j = 0; j < 64; ++j) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x) : "v"(x));
+  }
+  const uint64_t c1 = __builtin_readcyclecounter();
+  const uint64_t w1 = wall_clock64();
+  if (threadIdx.x == 0) {
+    out[0] = w1 - w0;
+    out[1] = c1 - c0;
+    out[2] = x;
+  }
+}
+
+hipError_t launch_clock_probe(uint64_t iters, uint64_t* d_out, hipStream_t stream) {
+  hipLaunchKernelGGL(clock_probe_kernel, dim3(1), dim3(64), 0, stream, iters, d_out);
+  return hipGetLastError();
+}
+
 hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, int cus, hipStream_t stream) {
   hipLaunchKernelGGL(copy_kernel, dim3((unsigned)cus * 16), dim3(256), 0, stream, (uint4*)dst, (const uint4*)src, bytes / 16);
   return hipGetLastError();

@@ -109,7 +109,10 @@ extern "C" int spd_kv_free(spd_pool* pool, uint64_t req_id, uint64_t* op_seq_out
   std::lock_guard<std::mutex> lk(pool->mu);
   auto it = pool->tables.find(req_id);
   if (it == pool->tables.end()) return SPD_ENOENT;
-  std::vector<int32_t>& t = it->second;
+  spd_req_table& t = it->second;
+  // pages go back on the free stack at once, so no step that took this table may still be running
+  for (int ph = 0; ph < 2; ++ph)
+    if (!spd::phase_step_done(pool->ctx, ph, t.last_use[ph])) return SPD_ESTATE;
   for (size_t i = t.size(); i-- > 0;) pool->free_stack.push_back(t[i]);
   pool->used -= (int64_t)t.size();
   pool->tables.erase(it);

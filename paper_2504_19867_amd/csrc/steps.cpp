@@ -42,12 +42,24 @@ static void build_tile_descs(const PoolGeom& g, const int32_t* bt, int32_t start
   }
 }
 
+// The kernels move 16 bytes per lane: every tensor a step is given must start on a 16-byte boundary.
+static bool misaligned16(const void* a, const void* b = nullptr, const void* c = nullptr, const void* d = nullptr,
+                         const void* e = nullptr) {
+  return (((uintptr_t)a | (uintptr_t)b | (uintptr_t)c | (uintptr_t)d | (uintptr_t)e) & 15) != 0;
+}
+
+// The number the phase's step now being prepared will carry (its staging slot's commit assigns it).
+static uint64_t next_step_number(spd_ctx* ctx, int phase) {
+  return ctx->phase[phase].issue_seq.load(std::memory_order_relaxed) + 1;
+}
+
 static int kv_copy(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int32_t start_pos, int32_t n_tokens,
                    const void* k, const void* v, bool write) {
   if (!ctx || !pool || pool->ctx != ctx || phase < 0 || phase > 1 || start_pos < 0 || n_tokens <= 0 || !k)
     return SPD_EINVAL;
   const PoolGeom& g = pool->geom;
   if ((g.kind == SPD_KV_GQA) != (v != nullptr)) return SPD_EINVAL;
+  if (misaligned16(k, v)) return SPD_EINVAL;
   if (ctx->device < 0) return SPD_ESTATE;
   std::vector<TileDesc> descs;
   {
@@ -57,6 +69,7 @@ static int kv_copy(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int
     int64_t need = ((int64_t)start_pos + n_tokens + g.P - 1) / g.P;
     if ((int64_t)it->second.size() < need) return SPD_EINVAL;
     build_tile_descs(g, it->second.data(), start_pos, n_tokens, 0, descs);
+    it->second.last_use[phase] = next_step_number(ctx, phase);
   }
   hipStream_t stream;
   int rc = phase_enter(ctx, phase, &stream);
@@ -65,12 +78,12 @@ static int kv_copy(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int
   spd_stage* st;
   if ((rc = stage_acquire(ctx, phase, bytes, &st)) != SPD_OK) return rc;
   memcpy(st->host, descs.data(), bytes);
-  if ((rc = stage_commit(ctx, phase, st, bytes, stream)) != SPD_OK) return rc;
+  if ((rc = stage_copy(st, bytes, stream)) != SPD_OK) return rc;
   if (write)
     SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)st->dev, (int)descs.size(), k, v, stream));
   else
     SPD_HIP(launch_kv_gather(g, pool->base, (const TileDesc*)st->dev, (int)descs.size(), (void*)k, (void*)v, stream));
-  return SPD_OK;
+  return stage_commit(ctx, phase, st, bytes, stream, false);
 }
 
 extern "C" int spd_kv_write(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int32_t start_pos,
@@ -96,6 +109,7 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
     if (!b->latent || b->n_kv_heads != b->n_q_heads) return SPD_EINVAL;
   }
   if (!prefill_shape_supported(b->dim_qk, b->dim_v)) return SPD_EINVAL;
+  if (misaligned16(b->q, b->k, b->v, b->out, b->latent)) return SPD_EINVAL;
   for (int r = 0; r < b->n_req; ++r) {
     if (b->cu_seqlens[r + 1] <= b->cu_seqlens[r]) return SPD_EINVAL;     // zero-length prompt
     for (int r2 = 0; r2 < r; ++r2)
@@ -123,9 +137,7 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
     }
   }
 
-  hipStream_t stream;
-  int rc = phase_enter(ctx, SPD_PHASE_PREFILL, &stream);
-  if (rc != SPD_OK) return rc;
+  int rc;
   // One persistent workgroup per compute unit of the prefill share, each with its chain of work
   // items, where such a launch gets one compute unit per workgroup: an XCD deals its workgroups to
   // its four shader arrays in turn, so every XCD must contribute a multiple of 4 compute units (the
@@ -134,11 +146,16 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   // hardware as compute units free up.
   // Nor where the two phases' masks overlap: a persistent workgroup keeps its compute unit for the
   // whole kernel, and decode workgroups that are allowed nowhere else would wait that long.
-  const int share = std::max(1, ctx->phase[SPD_PHASE_PREFILL].active_cus);
-  bool persistent = share % ctx->xcds == 0 && (share / ctx->xcds) % 4 == 0;
+  // The share is the one this step will run on: a staged partition is adopted below, once nothing but a HIP
+  // call can fail any more, so a step that returns an error of its own leaves the partition as it was.
+  int share;
+  bool persistent;
   {
     std::lock_guard<std::mutex> lk(ctx->part_mu);
-    const std::vector<uint32_t>& pm = ctx->phase[SPD_PHASE_PREFILL].active_mask;
+    const spd_phase_state& psx = ctx->phase[SPD_PHASE_PREFILL];
+    share = std::max(1, psx.has_pending ? psx.pending_cus : psx.active_cus);
+    persistent = share % ctx->xcds == 0 && (share / ctx->xcds) % 4 == 0;
+    const std::vector<uint32_t>& pm = psx.has_pending ? psx.pending_mask : psx.active_mask;
     const spd_phase_state& dsx = ctx->phase[SPD_PHASE_DECODE];
     const std::vector<uint32_t>& dm = dsx.has_pending ? dsx.pending_mask : dsx.active_mask;
     for (size_t i = 0; i < pm.size() && i < dm.size(); ++i)
@@ -147,7 +164,7 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
       for (size_t i = 0; i < pm.size() && i < dsx.active_mask.size(); ++i)
         if (pm[i] & dsx.active_mask[i]) persistent = false;
   }
-  if (const char* env = getenv("SPD_PREFILL_PERSISTENT")) persistent = atoi(env) != 0;   // experiment switch, read per call
+  if (ctx->env_prefill_persistent >= 0) persistent = ctx->env_prefill_persistent != 0;   // experiment switch
   std::vector<PrefillWork> work;
   std::vector<int32_t> chain;
   build_prefill_chains(b->cu_seqlens, chunked ? b->prefix_lens : nullptr, chunked ? kv_cu.data() : nullptr, b->n_req,
@@ -192,11 +209,15 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
     for (int r = 0; r < b->n_req; ++r) {
       const int32_t row0 = b->cu_seqlens[r], len = b->cu_seqlens[r + 1] - row0, pre = chunked ? b->prefix_lens[r] : 0;
       reserve_locked(pool, b->req_ids[r], pre + len);
-      const int32_t* table = pool->tables[b->req_ids[r]].data();
+      spd_req_table& entry = pool->tables[b->req_ids[r]];
+      entry.last_use[SPD_PHASE_PREFILL] = next_step_number(ctx, SPD_PHASE_PREFILL);
+      const int32_t* table = entry.data();
       build_tile_descs(g, table, pre, len, row0, descs);
       if (chunked) build_tile_descs(g, table, 0, pre + len, kv_cu[(size_t)r], gdescs);
     }
   }
+  hipStream_t stream;
+  if ((rc = phase_enter(ctx, SPD_PHASE_PREFILL, &stream)) != SPD_OK) return rc;
   memcpy(st->host, work.data(), work.size() * sizeof(PrefillWork));
   memcpy(st->host + off_chain, chain.data(), chain.size() * sizeof(int32_t));
   memcpy(st->host + off_desc, descs.data(), descs.size() * sizeof(TileDesc));
@@ -237,10 +258,9 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
 // ------------------------------------------------------------------------------------------ decode
 // Split-K chunk length in units (16-token tiles for GQA, 16-token steps for MLA).
 static int decode_chunk_units(spd_phase_state& ps, const int32_t* ctx_lens, int B, int unit_t, int64_t sum_units, int Hkv,
-                              int cus, bool mla) {
-  const char* env = getenv("SPD_DECODE_CHUNK_TILES");   // tuning override, read per call
+                              int cus, bool mla, int override_tiles) {
   const int64_t round = mla ? 1 : 8;              // GQA: 4 waves x 2 tiles per step
-  if (env && atoi(env) > 0) return (int)((atoi(env) + round - 1) / round * round);
+  if (override_tiles > 0) return (int)((override_tiles + round - 1) / round * round);   // tuning override
   if (mla) {
     // Two workgroups are resident per CU (slots); items are issued longest first and a slot takes
     // the next item when it is done, so a chunk length is judged by replaying exactly that: the
@@ -296,6 +316,7 @@ static int decode_step_impl(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch
   const bool append = b->k_new != nullptr;
   if (append && (g.kind == SPD_KV_GQA) != (b->v_new != nullptr)) return SPD_EINVAL;
   if (!append && b->v_new) return SPD_EINVAL;
+  if (misaligned16(b->q, b->out, b->k_new, b->v_new)) return SPD_EINVAL;
   for (int r = 0; r < b->n_req; ++r) {
     if (b->ctx_lens[r] <= 0) return SPD_EINVAL;                            // empty context
     if (append)
@@ -324,11 +345,17 @@ static int decode_step_impl(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch
   }
   const int bt_stride = max_pages;
 
-  hipStream_t stream;
-  int rc = phase_enter(ctx, SPD_PHASE_DECODE, &stream);
-  if (rc != SPD_OK) return rc;
+  // the share this step will run on: a staged partition is adopted further down, once nothing but a HIP call can
+  // fail any more, so a step that returns an error of its own leaves the partition as it was
+  int rc;
   spd_phase_state& ds = ctx->phase[SPD_PHASE_DECODE];
-  const int chunk_tiles = decode_chunk_units(ds, b->ctx_lens, B, unit_t, sum_tiles, g.Hkv, ds.active_cus, mla);
+  int share;
+  {
+    std::lock_guard<std::mutex> lk(ctx->part_mu);
+    share = ds.has_pending ? ds.pending_cus : ds.active_cus;
+  }
+  const int chunk_tiles = decode_chunk_units(ds, b->ctx_lens, B, unit_t, sum_tiles, g.Hkv, share, mla,
+                                             ctx->env_decode_chunk_tiles);
   const int max_chunks = (max_tiles + chunk_tiles - 1) / chunk_tiles;
 
   // work items (request, chunk), longest first: only chunks that exist are launched
@@ -389,7 +416,8 @@ static int decode_step_impl(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch
     }
     for (int r = 0; r < B; ++r) {
       if (append) reserve_locked(pool, b->req_ids[r], b->ctx_lens[r]);
-      const std::vector<int32_t>& t = pool->tables[b->req_ids[r]];
+      spd_req_table& t = pool->tables[b->req_ids[r]];
+      t.last_use[SPD_PHASE_DECODE] = next_step_number(ctx, SPD_PHASE_DECODE);
       int32_t pages = (b->ctx_lens[r] + g.P - 1) / g.P;
       h_ctx[r] = b->ctx_lens[r];
       memcpy(h_bt + (size_t)r * bt_stride, t.data(), sizeof(int32_t) * pages);
@@ -401,8 +429,10 @@ static int decode_step_impl(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch
       }
     }
   }
+  hipStream_t stream;
+  if ((rc = phase_enter(ctx, SPD_PHASE_DECODE, &stream)) != SPD_OK) return rc;
   if (timing) SPD_HIP(hipEventRecord(ds.ev_start, stream));
-  if ((rc = stage_commit(ctx, SPD_PHASE_DECODE, st, bytes, stream, true, sdev)) != SPD_OK) return rc;
+  if ((rc = stage_copy(st, bytes, stream, sdev)) != SPD_OK) return rc;
   const void* att_q = b->q;
   if (b->rope) {
     SPD_HIP(launch_rope_append(g, pool->base, (const TileDesc*)(sdev + off_desc), (const int32_t*)sdev, B, b->q, ws_q,
@@ -423,6 +453,9 @@ static int decode_step_impl(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch
                               bt_stride, sdev + off_items, n_items, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks,
                               (float*)(max_chunks > 1 ? ws : nullptr), (float*)(max_chunks > 1 ? ws + ws_o_bytes : nullptr), stream));
   if (timing && (rc = kernel_timing_mark(ctx, SPD_PHASE_DECODE, 1, stream)) != SPD_OK) return rc;
+  // the slot's event goes behind the attention kernels: it frees the staging slot and tells spd_kv_free that
+  // the step no longer reads its requests' pages
+  if ((rc = stage_commit(ctx, SPD_PHASE_DECODE, st, bytes, stream, false)) != SPD_OK) return rc;
   if (timing) {
     SPD_HIP(hipEventRecord(ds.ev_end, stream));
     ds.timed = true;

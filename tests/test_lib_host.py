@@ -253,6 +253,61 @@ def test_step_argument_validation():
     assert pool.stats()[2] == 1
 
 
+def test_misaligned_device_tensors_are_refused():
+    """Every tensor a step is given must start on a 16-byte boundary (the kernels move 16 bytes per lane): a view
+    that starts 2, 4 or 8 bytes into one is SPD_EINVAL; the same call with aligned addresses gets as far as
+    SPD_ESTATE on a host-only context."""
+    ctx, pool = host_pool(16, 16)
+    pool.kv_reserve(1, 16)
+    A = 4096
+
+    def prefill(q=A, k=A, v=A, out=A):
+        pool.prefill_step([2], [0, 8], q, k, v, out, 2, 2, 64, 64, 1.0)
+
+    def decode(q=A, out=A, k_new=None, v_new=None):
+        pool.decode_step([1], [4], q, out, 2, 1.0, k_new=k_new, v_new=v_new)
+
+    for off in (2, 4, 8):
+        bad = A + off
+        cases = [lambda: prefill(q=bad), lambda: prefill(k=bad), lambda: prefill(v=bad), lambda: prefill(out=bad),
+                 lambda: decode(q=bad), lambda: decode(out=bad), lambda: decode(k_new=bad, v_new=A),
+                 lambda: decode(k_new=A, v_new=bad), lambda: pool.kv_write(0, 1, 0, 4, bad, A),
+                 lambda: pool.kv_write(0, 1, 0, 4, A, bad), lambda: pool.kv_gather(0, 1, 4, bad, A),
+                 lambda: pool.decode_step_noalloc_batch(pool.make_decode_batch([1], [4], bad, A, 2, 1.0))]
+        for i, fn in enumerate(cases):
+            with pytest.raises(S.SpdError) as e:
+                fn()
+            assert e.value.status == S.SPD_EINVAL, (off, i)
+    for fn in (prefill, decode, lambda: decode(k_new=A, v_new=A), lambda: pool.kv_write(0, 1, 0, 4, A, A)):
+        with pytest.raises(S.SpdError) as e:
+            fn()
+        assert e.value.status == S.SPD_ESTATE
+    assert pool.stats()[2] == 1
+    # the MLA side: the latent rows of a prefill step
+    ctx2 = S.Context(-1)
+    mla = S.Pool(ctx2, None, 0, S.SPD_KV_MLA_LATENT, 64, 1, 576, 512, 8)
+    with pytest.raises(S.SpdError) as e:
+        mla.prefill_step([1], [0, 8], A, A, A, A, 4, 4, 192, 128, 1.0, latent=A + 8)
+    assert e.value.status == S.SPD_EINVAL
+    with pytest.raises(S.SpdError) as e:
+        mla.prefill_step([1], [0, 8], A, A, A, A, 4, 4, 192, 128, 1.0, latent=A)
+    assert e.value.status == S.SPD_ESTATE
+
+
+def test_free_needs_no_wait_when_no_step_took_the_table():
+    """The lifetime rule of spd_kv_free concerns steps in flight on the GPU; a request that no step was ever given
+    (all a host-only context can have) is freed at once, and its pages are the next ones handed out."""
+    ctx, pool = host_pool(8, 16)
+    pool.kv_reserve(1, 40)
+    table = pool.kv_block_table(1)
+    pool.kv_free(1)
+    with pytest.raises(S.SpdError) as e:
+        pool.kv_free(1)
+    assert e.value.status == S.SPD_ENOENT
+    pool.kv_reserve(2, 40)
+    assert pool.kv_block_table(2) == table
+
+
 # ---------------------------------------------------------------- SLO-aware partition adjuster
 def _feed(adj, ora, ttfts, tpots):
     for v in ttfts:
