@@ -54,6 +54,10 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the other single-GPU workloads (configs 3 and 4 at 50/50)")
     ap.add_argument("--no-clock", action="store_true", help="skip the clock probe beside the phases")
+    ap.add_argument("--no-solo", action="store_true",
+                    help="profiling aid: skip the solo passes, so that every launch of the run is in the headline regime")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="profiling aid: also run a plain 1 GiB copy kernel four times (known traffic for the byte counters)")
     ap.add_argument("--pool-gb", type=float, default=None, help="override pool size (GB)")
     ap.add_argument("--no-scramble", action="store_true", help="experiment: hand out physical pages in order")
     ap.add_argument("--decode-per-prefill", type=int, default=0,
@@ -371,8 +375,10 @@ def measure_config(cfg, args, steps, warmup, sweep, clock):
             wall_ms, _, _ = bench.run_concurrent(steps, r, only)                       # the timed region: K steps
             _, pk, dk = bench.run_concurrent(min(steps, 64), r, only, timing=True)     # same steps again, kernels bracketed by events
         else:
-            solo_p_k, solo_p_w = bench.time_solo(PRE, max(5, steps // 4))
-            solo_d_k, solo_d_w = bench.time_solo(DEC, max(10, steps))
+            solo_p_k = solo_p_w = solo_d_k = solo_d_w = float("nan")
+            if not args.no_solo:
+                solo_p_k, solo_p_w = bench.time_solo(PRE, max(5, steps // 4))
+                solo_d_k, solo_d_w = bench.time_solo(DEC, max(10, steps))
             run_async(bench, warmup)
             wall_ms, n_dec, _, _ = run_async(bench, steps)                              # the timed region: K prefill steps, decode free-running
             r = n_dec / steps
@@ -391,6 +397,14 @@ def measure_config(cfg, args, steps, warmup, sweep, clock):
                          "prefill_tflops": bench.prefill_flops / (solo_p_k * 1e-3) / 1e12,
                          "decode_gbs": solo_dec_gbs, "decode_frac_of_share_read": solo_dec_gbs / read_gbs}}
 
+    if args.calibrate_copy:
+        torch = bench.torch
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=bench.dev).random_()
+        b = torch.empty_like(a)
+        for _ in range(4):
+            bench.ctx.phase_copy(DEC, b, a, 1 << 30)
+        bench.ctx.phase_sync(DEC)
+        del a, b
     head = measure_split(p_pct, d_pct, steps, warmup, args.only)
     splits = [head]
     if sweep:
