@@ -21,10 +21,12 @@
 // 128 of the 512 output dims, so no cross-wave reduction is ever needed.  Split-K partials go to
 // the same workspace / combine kernel as the GQA path.
 //
-// With one wave per SIMD nothing hides latency but the wave's own instruction stream, so both
+// With two waves per SIMD little hides latency but the wave's own instruction stream, so both
 // products are software-pipelined: LDS operand reads run a ring of 8 operands ahead of the MFMAs,
-// and the score product accumulates into six independent accumulators (three per 16-token block)
-// so that back-to-back MFMAs never wait for each other's result.
+// the score product accumulates into three independent accumulators so that back-to-back MFMAs never
+// wait for each other's result, and the second product of a step is issued in the next iteration,
+// behind that step's first operand reads.  The loop reads no block table entry from memory and divides
+// nothing: the chunk's page ids sit in one register (lane i = the chunk's i-th page).
 #include "internal.h"
 
 namespace spd {
@@ -73,13 +75,10 @@ __device__ inline float mla_max_over_rows(float x) {
   asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(x), "+v"(y));
   return fmaxf(x, y);
 }
-#ifdef SPD_MLA_STAMPS
-__device__ unsigned long long g_mla_ph[8];
-#define MLA_STAMP(i) { unsigned long long now_ = __builtin_readcyclecounter(); ph[i] += now_ - tprev; tprev = now_; }
-#else
-#define MLA_STAMP(i)
-#endif
-#define SPD_MLA_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
+// wait until at most N of the wave's vector memory loads are outstanding and all of its LDS reads have returned
+// (the value operands read in the iteration before are used after the barrier, and the stage they came from is
+// loaded into again right behind it)
+#define SPD_MLA_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (0 << 8) | (((N) >> 4) << 14))
 
 // grid (n_items), block 256: work item = (request, chunk).  chunk_steps = 16-token steps per chunk.
 __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
@@ -164,20 +163,26 @@ __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
 #pragma unroll
   for (int t = 0; t < PD; ++t)
     if (t < n_steps) issue_loads(t);
-  // Draw the compiler's wait for the query loads to this point, after the first steps are on their
-  // way: left to itself it waits at their first use inside the loop, with a count that knows
+  // The loop itself touches neither the block table in memory nor a division: lane i of `pages` holds the id of
+  // the chunk's i-th page, the step to load next is tracked as (page, step inside the page).
+  const int page_first = step0 / steps_per_page;
+  const int n_pages_all = (n_steps_all + steps_per_page - 1) / steps_per_page;
+  const int pages = bt_row[min(page_first + lane, n_pages_all - 1)];   // a chunk spans at most 64 pages (the host sees to it)
+  int nl_page = (step0 + PD) / steps_per_page - page_first, nl_sub = (step0 + PD) % steps_per_page;
+  // Draw the compiler's wait for the query loads (and the page ids) to this point, after the first steps are on
+  // their way: left to itself it waits at their first use inside the loop, with a count that knows
   // nothing of the loads issued by hand, and every iteration would drain the prefetch queue.
 #pragma unroll
   for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(__builtin_bit_cast(uint4, qf[s]).x));
+  asm volatile("" ::"v"(pages));
 
   constexpr int RING = 8;
   static_assert(RING == VB, "all value operands of a step are read ahead");
-#ifdef SPD_MLA_STAMPS
-  unsigned long long ph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  unsigned long long tprev = __builtin_readcyclecounter();
-#endif
+  // The second product of a step is issued at the start of the next iteration, between that step's first operand
+  // reads and its first product, whose LDS latency it covers; the last one follows the loop.
+  s16x4 vring[RING];
+  uint2 pb = uint2{0u, 0u};
   for (int st = 0; st < n_steps; ++st) {
-    MLA_STAMP(0)
     // this wave's loads of step st are done when at most (steps issued after it) * (its loads per step) remain
     const int later = min(PD - 1, n_steps - 1 - st);
     if (five) {
@@ -189,12 +194,14 @@ __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
       else if (later == 1) SPD_MLA_WAIT_VMCNT(LPW - 1);
       else SPD_MLA_WAIT_VMCNT(0);
     }
-    MLA_STAMP(1)
     asm volatile("s_barrier" ::: "memory");        // step st has landed for all waves; stage of st - 1 is free
-    MLA_STAMP(2)
     const bool more = st + PD < n_steps;
-    const char* src_next = load_src(more ? st + PD : st);
-    MLA_STAMP(3)
+    const int page_next = __builtin_amdgcn_readlane(pages, nl_page & 63);
+    const char* src_next = pool + (uint64_t)page_next * page_bytes + (uint32_t)nl_sub * STAGE_BYTES;
+    if (++nl_sub == steps_per_page) {
+      nl_sub = 0;
+      ++nl_page;
+    }
 
     const char* stage = smem + (st % NSTAGE) * STAGE_BYTES;
     const int tok0 = (step0 + st) * STEP_T;         // first token of the step
@@ -216,6 +223,12 @@ __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
 #pragma unroll
     for (int o = 0; o < RING; ++o) ring[o] = read_s(o);
     __builtin_amdgcn_sched_barrier(0);              // keep the issue order below (reads stay ahead of their use)
+    if (st > 0) {                                   // O^T += C^T . P^T of the step before (never a context's last)
+#pragma unroll
+      for (int blk = 0; blk < VB; ++blk)
+        O[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vring[blk], __builtin_bit_cast(s16x4, pb), O[blk], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int sk = 0; sk < KS; ++sk) {
       acc[sk % 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ring[sk % RING]), qf[sk], acc[sk % 3], 0, 0, 0);
@@ -223,16 +236,13 @@ __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
       if (sk % 3 == 1 && sk / 3 < LPW && more) load_one(src_next, st + PD, sk / 3);
       __builtin_amdgcn_sched_barrier(0);
     }
-    MLA_STAMP(4)
     // value operands: in flight while the vector ALU does the softmax
-    s16x4 vring[RING];
 #pragma unroll
     for (int o = 0; o < RING; ++o) vring[o] = read_v(o);
     __builtin_amdgcn_sched_barrier(0);
     f32x4 S = acc[0] + acc[1] + acc[2];
     // lane holds, for head col, tokens tok0 + 4 c4 + i
-    const bool tail = tok0 + STEP_T > n;
-    if (tail) {
+    if (tok0 + STEP_T > n) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (tok0 + 4 * c4 + i >= n) S[i] = -INFINITY;
@@ -245,7 +255,7 @@ __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(S[i] * c - mc);
     const float psum = (p[0] + p[1]) + (p[2] + p[3]);
-    const uint2 pb = uint2{mla_pack_bf16(p[0], p[1]), mla_pack_bf16(p[2], p[3])};
+    pb = uint2{mla_pack_bf16(p[0], p[1]), mla_pack_bf16(p[2], p[3])};
     if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {        // rescale only when some running maximum moved
       const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
       l *= alpha;
@@ -254,34 +264,21 @@ __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
       m = m_new;
     }
     l += psum;
-    // ---- O^T += C^T . P^T for this wave's 128 dims.  Tokens of this lane's operand:
-    // tok0 + 4 c4 + {0..3}; slots past the context hold arbitrary bytes and are cleared.
-    MLA_STAMP(5)
-    __builtin_amdgcn_sched_barrier(0);
-    if (!tail) {
+  }
+  // ---- the last step's second product.  Tokens of this lane's operand: tok_last + 4 c4 + {0..3}; slots past the
+  // context hold arbitrary bytes and are cleared (their weights are zero, but 0 x NaN is not).
+  {
+    const int t0 = (step0 + n_steps - 1) * STEP_T + 4 * c4;
+    const uint32_t m01 = (t0 + 0 < n ? 0x0000ffffu : 0u) | (t0 + 1 < n ? 0xffff0000u : 0u);
+    const uint32_t m23 = (t0 + 2 < n ? 0x0000ffffu : 0u) | (t0 + 3 < n ? 0xffff0000u : 0u);
 #pragma unroll
-      for (int blk = 0; blk < VB; ++blk)
-        O[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vring[blk], __builtin_bit_cast(s16x4, pb), O[blk], 0, 0, 0);
-    } else {                                        // last step of the context
-      const int t0 = tok0 + 4 * c4;
-      const uint32_t m01 = (t0 + 0 < n ? 0x0000ffffu : 0u) | (t0 + 1 < n ? 0xffff0000u : 0u);
-      const uint32_t m23 = (t0 + 2 < n ? 0x0000ffffu : 0u) | (t0 + 3 < n ? 0xffff0000u : 0u);
-#pragma unroll
-      for (int blk = 0; blk < VB; ++blk) {
-        uint2 r = __builtin_bit_cast(uint2, vring[blk]);
-        r.x &= m01;
-        r.y &= m23;
-        O[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, r), __builtin_bit_cast(s16x4, pb), O[blk], 0, 0, 0);
-      }
+    for (int blk = 0; blk < VB; ++blk) {
+      uint2 r = __builtin_bit_cast(uint2, vring[blk]);
+      r.x &= m01;
+      r.y &= m23;
+      O[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, r), __builtin_bit_cast(s16x4, pb), O[blk], 0, 0, 0);
     }
-    MLA_STAMP(6)
   }
-#ifdef SPD_MLA_STAMPS
-  if (lane == 0 && wave == 1) {
-    for (int i = 0; i < 7; ++i) atomicAdd(&g_mla_ph[i], ph[i]);
-    atomicAdd(&g_mla_ph[7], (unsigned long long)n_steps);
-  }
-#endif
 
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
@@ -332,14 +329,6 @@ __global__ __launch_bounds__(512) void decode_mla_combine_kernel(bf16_t* __restr
   out[((size_t)b * H + h) * mla::DV + d] = (bf16_t)(mla_pack_bf16(o / l_tot, 0.f) & 0xffffu);
 }
 
-#ifdef SPD_MLA_STAMPS
-extern "C" int spd_debug_mla_phases(unsigned long long* out8, int reset) {
-  unsigned long long z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_mla_ph), sizeof(z)) != hipSuccess) return -1;
-  if (reset && hipMemcpyToSymbol(HIP_SYMBOL(g_mla_ph), z, sizeof(z)) != hipSuccess) return -1;
-  return 0;
-}
-#endif
 int decode_mla_step_tokens() { return mla::STEP_T; }
 
 hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const void* q, void* out,
@@ -347,6 +336,8 @@ hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const voi
                              const void* d_items, int n_items, int B, int H, float scale, int chunk_steps,
                              int max_chunks, float* ws_o, float* ws_ml, hipStream_t stream) {
   const float c = scale * 1.4426950408889634f;
+  // the kernel keeps a chunk's page ids in the 64 lanes of one register
+  if (chunk_steps <= 0 || (chunk_steps + g.P / mla::STEP_T - 1) / (g.P / mla::STEP_T) + 1 > 64) return hipErrorInvalidValue;
   hipLaunchKernelGGL(decode_mla_kernel, dim3((unsigned)n_items), dim3(256), 0, stream, pool_base, g.page_bytes,
                      g.P / mla::STEP_T, (const bf16_t*)q, (bf16_t*)out, d_ctx_lens, d_block_tables, bt_stride,
                      (const int2*)d_items, H, c, chunk_steps, max_chunks, ws_o, ws_ml);

@@ -354,8 +354,11 @@ static int decode_step_impl(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch
     std::lock_guard<std::mutex> lk(ctx->part_mu);
     share = ds.has_pending ? ds.pending_cus : ds.active_cus;
   }
-  const int chunk_tiles = decode_chunk_units(ds, b->ctx_lens, B, unit_t, sum_tiles, g.Hkv, share, mla,
-                                             ctx->env_decode_chunk_tiles);
+  int chunk_tiles = decode_chunk_units(ds, b->ctx_lens, B, unit_t, sum_tiles, g.Hkv, share, mla,
+                                       ctx->env_decode_chunk_tiles);
+  // the MLA kernel keeps the page ids of a chunk in the 64 lanes of one register: at most 63 pages per chunk
+  // (a chunk that starts inside a page touches one more than it holds)
+  if (mla) chunk_tiles = std::min(chunk_tiles, 62 * (g.P / unit_t));
   const int max_chunks = (max_tiles + chunk_tiles - 1) / chunk_tiles;
 
   // work items (request, chunk), longest first: only chunks that exist are launched
