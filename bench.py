@@ -227,6 +227,45 @@ class Bench:
         w, c, _, _ = (int(x) for x in buf.cpu().tolist())
         return {"mhz": 100.0 * c / max(w, 1), "cycles_per_add": c / (64.0 * iters), "probe_ms": w / 1e5}
 
+    def partition_switch(self):
+        """Cost of a resize: spd_set_partition for a split never seen (streams are created) and for one seen
+        before (streams re-used), on the caller's thread; and what the swap costs the phases: the step that adopts
+        the staged partition against a steady step, each timed from the call to the drain of its phase."""
+        def one_step(fn, phase):
+            t0 = time.perf_counter()
+            fn()
+            self.ctx.phase_sync(phase)
+            return (time.perf_counter() - t0) * 1e3
+
+        def set_ms(p, d):
+            t0 = time.perf_counter()
+            self.ctx.set_partition(p, d)
+            return (time.perf_counter() - t0) * 1e3
+
+        total, half = self.total_cus, self.total_cus // 2
+        self.sync()
+        a, b = (half, half), (half - self.gran, half + self.gran)       # 128/128 and 96/160 on this chip
+        self.ctx.set_partition(*a)
+        self.prefill(); self.decode(); self.sync()
+        new_ms = set_ms(*b)                                               # 96/160: not used anywhere else in this run
+        self.prefill(); self.decode(); self.sync()
+        reuse = []
+        steady = {"prefill": [], "decode": []}
+        swap = {"prefill": [], "decode": []}
+        for i in range(6):
+            for _ in range(3):
+                steady["prefill"].append(one_step(self.prefill, PRE))
+                steady["decode"].append(one_step(self.decode, DEC))
+            reuse.append(set_ms(*(a if i % 2 == 0 else b)))
+            swap["prefill"].append(one_step(self.prefill, PRE))           # these two steps adopt the staged streams
+            swap["decode"].append(one_step(self.decode, DEC))
+        self.ctx.set_partition(*a)
+        self.prefill(); self.decode(); self.sync()
+        return {"set_partition_new_split_ms": new_ms, "set_partition_seen_split_ms": median(reuse),
+                "steady_step_ms": {k: median(v) for k, v in steady.items()},
+                "step_that_adopts_ms": {k: median(v) for k, v in swap.items()},
+                "note": "steps timed one at a time, call to drain (host launch latency included in both rows)"}
+
     def time_solo(self, phase, n):
         """median kernel-level and step-level ms of `n` back-to-back steps of one phase, other phase idle"""
         fn = self.prefill if phase == PRE else self.decode
@@ -411,10 +450,11 @@ def measure_config(cfg, args, steps, warmup, sweep, clock):
         for pp, dp in list(cfg.cu_splits) + [(100, 100)]:
             if (pp, dp) != (p_pct, d_pct):
                 splits.append(measure_split(pp, dp, max(10, steps // 2), 2))
-    clocks = None
+    clocks = switch = None
     if clock:
         bench.set_split(p_pct, d_pct)
         clocks = {load: bench.clock_probe(load) for load in ("idle", "prefill", "decode", "both")}
+        switch = bench.partition_switch()
 
     r = head["decode_per_prefill"]
     tokens_per_step = (bench.T if args.only != "decode" else 0) + (r * bench.B if args.only != "prefill" else 0)
@@ -451,6 +491,7 @@ def measure_config(cfg, args, steps, warmup, sweep, clock):
     }
     if clocks:
         part["clock_probe"] = clocks
+        part["partition_switch"] = switch
     bench.close()
     del bench
     gc.collect()

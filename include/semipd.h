@@ -372,6 +372,12 @@ int spd_partition_masks(int total_cus, int granularity, int prefill_cus, int dec
  * per window, with lambda from the integer grid 0 .. min(x) - 1 (smallest squared error; a larger
  * lambda must win by more than 1e-12 (1 + error)); and uses Eq. 1 alone (b = 0, lambda = 0,
  * a = latency * share of the latest point) while all points of a phase sit at one share.
+ * Points are kept at the raw share (x0, y0) and the models are evaluated at the normalised share, as the
+ * printed algorithm does.  Where the shares overlap (x + y > 100, e.g. the initial (100, 100)) a model
+ * fitted at share 100 is therefore asked about share 50 and predicts about twice the observed latency:
+ * the phase that fails its objective then takes all max_step steps of its first adjustment, and since a
+ * share cannot pass 100 the other phase's share is lowered instead ((100, 100) -> (100, 60) with the
+ * defaults).  From the second window on the fit has two shares and follows the data.
  */
 typedef struct spd_ctrl spd_ctrl;
 typedef struct spd_ctrl_config {

@@ -20,11 +20,9 @@
 // LDS; the four 16-byte chunks of a row are XOR-swizzled with bits 2..3 of the row number, which
 // spreads 16 consecutive rows over all banks.
 //
-// Decode batches (ffn_gate_up_small_kernel, up to 256 tokens): the product is bound by reading the
-// weights once, so the work is cut into many small workgroups instead: 64 tokens x 64 joint columns
-// (32 outputs), the four waves taking every fourth 64-wide block of hidden straight from global
-// memory into registers (whole 128-byte lines of every weight row) and adding their partial sums
-// through LDS at the end.
+// Decode batches (up to 256 tokens) are bound by reading the weights once: the same kernel with smaller
+// tiles (128 x 128 with four waves, 64 x 128 with a ring of six stages; two workgroups per compute unit),
+// so that every compute unit of the share has a workgroup and more weight bytes are in flight per unit.
 #include "internal.h"
 
 namespace spd {

@@ -352,6 +352,9 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     // all unless the row sum says that the reference is out of range (an item's first tile, where
     // m = -inf makes every p infinite or NaN, or a tile whose scores exceed the reference by 2^60):
     // then the reference moves to the true maximum, the accumulators are rescaled, and p is redone.
+    // The softmax runs at raised priority: its vector instructions then slip in between the other wave's MFMAs
+    // (which hold that wave, not the vector unit), instead of queueing behind them.
+    __builtin_amdgcn_s_setprio(3);
     uint32_t pb[2][8];
     auto softmax_p = [&](float mc) -> float {
       float ls[4] = {0.f, 0.f, 0.f, 0.f};
@@ -401,6 +404,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
       psum = softmax_p(m * c);
     }
     l += psum;
+    __builtin_amdgcn_s_setprio(0);
 
     // ---- O^T += V^T . P^T : 16-key step kk multiplies with S^T block kk/2, registers 8*(kk%2) .. +7;
     // the operands of step kk + 1 are read while step kk multiplies

@@ -338,6 +338,24 @@ def test_adjuster_matches_hand_worked_trace_and_oracle():
         adj.close()
 
 
+def test_adjuster_from_the_overlapping_start_takes_every_step():
+    """Points are recorded at the raw share and Eq. 4 is evaluated at the normalised one (Algorithm 1 updates with x
+    and estimates with x'): from the library's initial (100, 100) the model fitted at share 100 is asked about share
+    50 and predicts twice the observed latency, so a phase that misses its objective by 1 % still takes all max_step
+    steps; the other share pays, since 100 cannot be passed.  Library and oracle agree on it."""
+    from oracle import controller as OC
+    for which in ("ttft", "tpot"):
+        adj, ora = S.Adjuster(100.0, 20.0, 90.0, 1, 4, 10), OC.Adjuster(100.0, 20.0, 90.0, 1, 4, 10)
+        ttft, tpot = (101.0, 10.0) if which == "ttft" else (50.0, 20.2)
+        _feed(adj, ora, [ttft] * 10, [tpot] * 10)
+        got = adj.step(0, 100, 100)
+        assert got == ora.step(0, 100, 100)
+        assert got == ((100, 60) if which == "ttft" else (60, 100))
+        # the next window, observed at the new partition, gives the fit a second share and the model its slope
+        _feed(adj, ora, [ttft * 0.7] * 10, [tpot * 0.7] * 10)
+        assert adj.step(1, *got) == ora.step(1, *got) == got
+
+
 def test_adjuster_decisions_bit_exact_and_model_close_on_random_streams():
     import random
     from oracle import controller as OC
