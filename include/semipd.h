@@ -161,7 +161,16 @@ int spd_kv_gather(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int3
  * prefix + len tokens, writes the new rows to the pages, gathers each request's rows
  * 0 .. prefix+len-1 through its block table into a library workspace and attends over that.  A
  * request with prefix > 0 must exist with at least prefix tokens reserved (else SPD_ENOENT /
- * SPD_EINVAL). */
+ * SPD_EINVAL).
+ *
+ * With `rope` non-NULL (GQA pools only; spd_rope_config is declared further down; paper, Evaluation
+ * "Implementation based on DistServe": the RoPE kernel) q and k are the vectors BEFORE the rotary
+ * embedding and the step rotates them itself, IN PLACE (q and k hold the rotated vectors afterwards,
+ * as after spd_rope_qk), row i of request r by position prefix_lens[r] + i: the keys on their way
+ * into the pages, in the launch that writes the pages (so K crosses memory once for rotation and
+ * page write together), the queries in a pass of their own before the attention.  The rotating range
+ * must fit the head (rotary_offset + rotary_dim <= dim_qk; multiples of 8 and 16), else SPD_EINVAL. */
+struct spd_rope_config;
 typedef struct {
   int32_t n_req;
   const uint64_t* req_ids;   /* host [n_req] */
@@ -177,6 +186,7 @@ typedef struct {
   int32_t dim_v;
   float scale;
   const int32_t* prefix_lens; /* host [n_req] or NULL (no cached prefix) */
+  const struct spd_rope_config* rope; /* NULL, or: q and k are given before RoPE and rotated by the step */
 } spd_prefill_batch;
 int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_batch* batch);
 
@@ -201,7 +211,6 @@ int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_batch* batc
  * workspace (the caller's q, k_new are left as they are), the key straight into the page, in the one
  * launch that appends; the attention then reads the rotated query.  The rotating range must fit the
  * head (rotary_offset + rotary_dim <= dim_k; multiples of 8 and 16) or the call is SPD_EINVAL. */
-struct spd_rope_config;
 typedef struct {
   int32_t n_req;
   const uint64_t* req_ids; /* host [n_req] */

@@ -66,7 +66,7 @@ struct TileDesc {
   int32_t sub;       // tile index inside the page
   int32_t t_begin;   // first token slot (0..15) touched
   int32_t t_end;     // one past the last token slot touched
-  int32_t pad[3];
+  int32_t pad[3];    // pad[0]: logical position of the tile's token slot 0 in its request
 };
 
 // Prefill work item = one workgroup: one tile of query rows of one request, for a group of query
@@ -180,9 +180,13 @@ void rope_frequencies(const spd_rope_config* c, double* out);
 // kernel launchers (kernels_*.hip); all enqueue on `stream` and return the launch status
 // d_tiles may be device-readable pinned host memory.  With copy_dst non-null the same launch also
 // copies copy_bytes (rounded up to 16) from copy_src to copy_dst.
+// With rope_w non-null (device or device-readable pinned: rot / 2 frequencies) the key rows are rotated on the way
+// (position = TileDesc.pad[0] + token slot), into the pages and in place in k; only where kv_write_can_rotate.
 hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d_tiles, int n_tiles,
                            const void* k, const void* v, hipStream_t stream, void* copy_dst = nullptr,
-                           const void* copy_src = nullptr, uint64_t copy_bytes = 0);
+                           const void* copy_src = nullptr, uint64_t copy_bytes = 0, const double* rope_w = nullptr,
+                           int rot = 0, int rot_off = 0, bool interleaved = false);
+bool kv_write_can_rotate(const PoolGeom& g);
 hipError_t launch_kv_gather(const PoolGeom& g, const char* pool_base, const TileDesc* d_tiles, int n_tiles,
                             void* k_out, void* v_out, hipStream_t stream);
 hipError_t launch_decode_gqa(const PoolGeom& g, const char* pool_base, const void* q, void* out,

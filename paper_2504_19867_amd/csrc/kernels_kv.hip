@@ -115,13 +115,33 @@ __global__ __launch_bounds__(256) void kv_write_kernel(char* __restrict__ base, 
 // up to HG KV heads: the descriptor (possibly in pinned host memory) is fetched once per group
 // instead of once per head, and the row reads of all the group's heads are in flight together
 // before the first head goes through LDS.  grid (n_tiles + copy_cols, ceil(Hkv / HG)), block 256.
-template <int HG>
+// With ROPE the key rows are rotated on the way (rotary position embedding, token position = pos0 of the tile's
+// descriptor + token slot; same arithmetic as rope_kernel: fp64 angle reduced to [-pi, pi], fp32 rotation, one
+// rounding to bf16): the rotated piece goes to the page and back to the caller's k row, which the attention
+// kernel of the same step reads.  A piece's partner (the other half of its pairs, in the half layout) is found
+// in the LDS copy of the raw row.
+struct RopeFuse {
+  const double* w;        // [rot / 2] frequencies
+  bf16_t* k_rw;           // the k tensor again, writable
+  int rot, off;           // rotating entries per head, first rotating entry (multiples of 16 and 8)
+  int interleaved;
+};
+
+__device__ inline float kv_bf_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ inline float kv_bf_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+__device__ inline uint32_t kv_pack_bf16(float a, float b) {
+  typedef float f32x2_ __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_ __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_{a, b}, bf16x2_));
+}
+
+template <int HG, bool ROPE>
 __global__ __launch_bounds__(256) void kv_write_heads_kernel(char* __restrict__ base, uint64_t page_bytes, uint32_t head_bytes,
                                                              uint32_t tile_bytes, uint32_t tile_k_bytes,
                                                              const TileDesc* __restrict__ descs, const bf16_t* __restrict__ k,
                                                              const bf16_t* __restrict__ v, int Hkv, int dk, int dv, int n_tiles,
                                                              uint4* __restrict__ copy_dst, const uint4* __restrict__ copy_src,
-                                                             uint64_t copy_n16) {
+                                                             uint64_t copy_n16, RopeFuse rp) {
   if ((int)blockIdx.x >= n_tiles) {
     const uint64_t blk = (uint64_t)(blockIdx.x - n_tiles) * gridDim.y + blockIdx.y;
     const uint64_t stride = (uint64_t)(gridDim.x - n_tiles) * gridDim.y * blockDim.x;
@@ -145,6 +165,30 @@ __global__ __launch_bounds__(256) void kv_write_heads_kernel(char* __restrict__ 
     if (g < ng && v_ok) vr[g] = load_once(v + ((size_t)(d.src_row + tv - d.t_begin) * Hkv + g0 + g) * dv + cv * 8);
   }
   const int v_items = (dv >> 5) * 64;
+  // the piece this thread carries to the page: token slot t_out, piece c_out of the row
+  const int t_out = i & 15, c_out = i >> 4;
+  const bool out_ok = i < ck_n * TILE_T && t_out >= d.t_begin && t_out < d.t_end;
+  float cs[8], sn[8];
+  int partner = -1;                                  // half layout: the piece that holds the other entry of each pair
+  bool rotates = false, second = false;
+  if constexpr (ROPE) {
+    const int e0 = 8 * c_out - rp.off;               // the piece's first entry, counted from the rotating range's start
+    rotates = out_ok && e0 >= 0 && e0 < rp.rot;
+    if (rotates) {
+      const int half = rp.rot >> 1;
+      second = !rp.interleaved && e0 >= half;
+      partner = rp.interleaved ? c_out : (second ? c_out - (half >> 3) : c_out + (half >> 3));
+      const int pair0 = rp.interleaved ? (e0 >> 1) : (second ? e0 - half : e0);
+      const double p = (double)(d.pad[0] + t_out);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (rp.interleaved && j >= 4) break;
+        const double turns = p * rp.w[pair0 + j] * 0.15915494309189535;   // angle / 2 pi
+        const float r = (float)((turns - __builtin_rint(turns)) * 6.283185307179586);
+        sincosf(r, &sn[j], &cs[j]);
+      }
+    }
+  }
 #pragma unroll
   for (int g = 0; g < HG; ++g) {
     if (g >= ng) break;
@@ -153,9 +197,33 @@ __global__ __launch_bounds__(256) void kv_write_heads_kernel(char* __restrict__ 
     if (v_ok) *(uint4*)&vs[tv][cv * 8] = vr[g];
     __syncthreads();
     // K part [chunk][token][8 dims]
-    if (i < ck_n * TILE_T) {
-      const int t = i & 15, c = i >> 4;
-      if (t >= d.t_begin && t < d.t_end) store_once(tile + ((size_t)(c * 16 + t) << 4), ks[t][c]);
+    if (out_ok) {
+      uint4 piece = ks[t_out][c_out];
+      if constexpr (ROPE) {
+        if (rotates) {
+          uint32_t x[4] = {piece.x, piece.y, piece.z, piece.w};
+          if (rp.interleaved) {                       // word j holds pair j: low half a, high half b
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float xa = kv_bf_lo(x[j]), xb = kv_bf_hi(x[j]);
+              x[j] = kv_pack_bf16(xa * cs[j] - xb * sn[j], xb * cs[j] + xa * sn[j]);
+            }
+          } else {
+            const uint4 other = ks[t_out][partner];
+            const uint32_t y[4] = {other.x, other.y, other.z, other.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float m0 = kv_bf_lo(x[j]), m1 = kv_bf_hi(x[j]), o0 = kv_bf_lo(y[j]), o1 = kv_bf_hi(y[j]);
+              // first half: mine is a (a cos - b sin); second half: mine is b (b cos + a sin)
+              x[j] = second ? kv_pack_bf16(m0 * cs[2 * j] + o0 * sn[2 * j], m1 * cs[2 * j + 1] + o1 * sn[2 * j + 1])
+                            : kv_pack_bf16(m0 * cs[2 * j] - o0 * sn[2 * j], m1 * cs[2 * j + 1] - o1 * sn[2 * j + 1]);
+            }
+          }
+          piece = uint4{x[0], x[1], x[2], x[3]};
+          *(uint4*)(rp.k_rw + ((size_t)(d.src_row + t_out - d.t_begin) * Hkv + g0 + g) * dk + c_out * 8) = piece;
+        }
+      }
+      store_once(tile + ((size_t)(c_out * 16 + t_out) << 4), piece);
     }
     // V part [d/32][token quad][d%16][(d/16)%2][4 tokens]
     if (i < v_items) {
@@ -311,8 +379,13 @@ hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, int cus, hipS
   return hipGetLastError();
 }
 
+bool kv_write_can_rotate(const PoolGeom& g) {
+  return g.kind == SPD_KV_GQA && g.dk <= 128 && g.dv <= 128 && g.Hkv >= 2;
+}
+
 hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d_tiles, int n_tiles, const void* k,
-                           const void* v, hipStream_t stream, void* copy_dst, const void* copy_src, uint64_t copy_bytes) {
+                           const void* v, hipStream_t stream, void* copy_dst, const void* copy_src, uint64_t copy_bytes,
+                           const double* rope_w, int rot, int rot_off, bool interleaved) {
   const uint64_t n16 = copy_dst ? (copy_bytes + 15) / 16 : 0;
   const int copy_cols = n16 ? (int)std::min<uint64_t>(16, (n16 + 256ull * g.Hkv - 1) / (256ull * g.Hkv)) : 0;
   if (n_tiles <= 0 && copy_cols == 0) return hipSuccess;
@@ -321,11 +394,18 @@ hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d
     const int groups = (g.Hkv + HG - 1) / HG;
     // the metadata copy keeps its share of workgroups: copy_cols x Hkv of them before, the same number now
     const int cols = copy_cols ? (copy_cols * g.Hkv + groups - 1) / groups : 0;
-    hipLaunchKernelGGL(kv_write_heads_kernel<HG>, dim3(n_tiles + cols, groups), dim3(256), 0, stream, pool_base, g.page_bytes,
-                       g.head_bytes, g.tile_bytes, g.tile_k_bytes, d_tiles, (const bf16_t*)k, (const bf16_t*)v, g.Hkv, g.dk,
-                       g.dv, n_tiles, (uint4*)copy_dst, (const uint4*)copy_src, n16);
+    RopeFuse rp{rope_w, (bf16_t*)const_cast<void*>(k), rot, rot_off, interleaved ? 1 : 0};
+    if (rope_w)
+      hipLaunchKernelGGL((kv_write_heads_kernel<HG, true>), dim3(n_tiles + cols, groups), dim3(256), 0, stream, pool_base,
+                         g.page_bytes, g.head_bytes, g.tile_bytes, g.tile_k_bytes, d_tiles, (const bf16_t*)k, (const bf16_t*)v,
+                         g.Hkv, g.dk, g.dv, n_tiles, (uint4*)copy_dst, (const uint4*)copy_src, n16, rp);
+    else
+      hipLaunchKernelGGL((kv_write_heads_kernel<HG, false>), dim3(n_tiles + cols, groups), dim3(256), 0, stream, pool_base,
+                         g.page_bytes, g.head_bytes, g.tile_bytes, g.tile_k_bytes, d_tiles, (const bf16_t*)k, (const bf16_t*)v,
+                         g.Hkv, g.dk, g.dv, n_tiles, (uint4*)copy_dst, (const uint4*)copy_src, n16, rp);
     return hipGetLastError();
   }
+  if (rope_w) return hipErrorInvalidValue;          // callers ask kv_write_can_rotate first
   hipLaunchKernelGGL(kv_write_kernel, dim3(n_tiles + copy_cols, g.Hkv), dim3(256), 0, stream, pool_base, g.page_bytes,
                      g.head_bytes, g.tile_bytes, g.tile_k_bytes, d_tiles, (const bf16_t*)k, (const bf16_t*)v, g.Hkv, g.dk,
                      g.dv, g.kind == SPD_KV_MLA_LATENT ? 1 : 0, n_tiles, (uint4*)copy_dst, (const uint4*)copy_src, n16);

@@ -37,6 +37,7 @@ static void build_tile_descs(const PoolGeom& g, const int32_t* bt, int32_t start
     d.sub = tile % g.tiles_per_page;
     d.t_begin = t_begin;
     d.t_end = t_end;
+    d.pad[0] = tile * TILE_T;
     out.push_back(d);
     pos += t_end - t_begin;
   }
@@ -110,6 +111,13 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   }
   if (!prefill_shape_supported(b->dim_qk, b->dim_v)) return SPD_EINVAL;
   if (misaligned16(b->q, b->k, b->v, b->out, b->latent)) return SPD_EINVAL;
+  if (b->rope) {
+    if (g.kind != SPD_KV_GQA) return SPD_EINVAL;
+    int rrc = rope_config_check(b->rope);
+    if (rrc != SPD_OK) return rrc;
+    if (b->rope->rotary_dim % 16 || b->rope->rotary_offset % 8 || b->rope->rotary_offset + b->rope->rotary_dim > b->dim_qk)
+      return SPD_EINVAL;
+  }
   for (int r = 0; r < b->n_req; ++r) {
     if (b->cu_seqlens[r + 1] <= b->cu_seqlens[r]) return SPD_EINVAL;     // zero-length prompt
     for (int r2 = 0; r2 < r; ++r2)
@@ -180,7 +188,11 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   size_t off_chain = align16(work.size() * sizeof(PrefillWork));
   size_t off_desc = align16(off_chain + chain.size() * sizeof(int32_t));
   size_t off_gather = align16(off_desc + n_descs * sizeof(TileDesc));
-  size_t bytes = off_gather + n_gather * sizeof(TileDesc);
+  // RoPE inside the step: the frequency table, and every row's position for the rotation of q
+  const int32_t n_rows = b->cu_seqlens[b->n_req];
+  size_t off_w = align16(off_gather + n_gather * sizeof(TileDesc));
+  size_t off_pos = align16(off_w + (b->rope ? sizeof(double) * (size_t)(b->rope->rotary_dim / 2) : 0));
+  size_t bytes = off_pos + (b->rope ? sizeof(int32_t) * (size_t)n_rows : 0);
   spd_stage* st;
   if ((rc = stage_acquire(ctx, SPD_PHASE_PREFILL, bytes, &st)) != SPD_OK) return rc;
   char* ws = nullptr;
@@ -222,6 +234,13 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   memcpy(st->host + off_chain, chain.data(), chain.size() * sizeof(int32_t));
   memcpy(st->host + off_desc, descs.data(), descs.size() * sizeof(TileDesc));
   if (chunked) memcpy(st->host + off_gather, gdescs.data(), gdescs.size() * sizeof(TileDesc));
+  if (b->rope) {
+    rope_frequencies(b->rope, (double*)(st->host + off_w));
+    int32_t* pos = (int32_t*)(st->host + off_pos);
+    for (int r = 0; r < b->n_req; ++r)
+      for (int32_t i = b->cu_seqlens[r]; i < b->cu_seqlens[r + 1]; ++i)
+        pos[i] = (chunked ? b->prefix_lens[r] : 0) + (i - b->cu_seqlens[r]);
+  }
   spd_phase_state& ps = ctx->phase[SPD_PHASE_PREFILL];
   if (ctx->kernel_timing) SPD_HIP(hipEventRecord(ps.ev_start, stream));
   const void* page_src_k = g.kind == SPD_KV_GQA ? b->k : b->latent;
@@ -231,8 +250,20 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
   // where the attention kernel (and the gather of a chunked step) find their lists
   void* host_dev = nullptr;
   if ((rc = stage_host_as_device(st, &host_dev)) != SPD_OK) return rc;
+  const spd_rope_config* rc_ = b->rope;
+  const bool fused = rc_ && kv_write_can_rotate(g);
+  if (rc_ && !fused)        // no fused form for this pool shape: q and k in one pass of their own, before the page write
+    SPD_HIP(launch_rope((void*)b->q, b->n_q_heads, (void*)b->k, b->n_kv_heads, b->dim_qk, rc_->rotary_dim, rc_->rotary_offset,
+                        rc_->interleaved != 0, n_rows, (const int32_t*)((const char*)host_dev + off_pos),
+                        (const double*)((const char*)host_dev + off_w), stream));
   SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)((const char*)host_dev + off_desc), (int)descs.size(), page_src_k,
-                          page_src_v, stream, st->dev, host_dev, bytes));
+                          page_src_v, stream, st->dev, host_dev, bytes,
+                          fused ? (const double*)((const char*)host_dev + off_w) : nullptr, fused ? rc_->rotary_dim : 0,
+                          fused ? rc_->rotary_offset : 0, fused && rc_->interleaved != 0));
+  if (fused)                // the keys were rotated on their way into the pages (and in place); the queries here
+    SPD_HIP(launch_rope((void*)b->q, b->n_q_heads, nullptr, 0, b->dim_qk, rc_->rotary_dim, rc_->rotary_offset,
+                        rc_->interleaved != 0, n_rows, (const int32_t*)(st->dev + off_pos), (const double*)(st->dev + off_w),
+                        stream));
   const void *att_k = b->k, *att_v = b->v;
   if (chunked) {
     // every request's rows 0 .. prefix+len-1, the new ones included, back out of the pages

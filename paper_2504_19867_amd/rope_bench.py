@@ -38,6 +38,44 @@ def main():
             nbytes = 2 * T * (HQ + HKV) * D * 2
             cus = split[0] if phase == PRE else split[1]
             print(f"{name:24s} on {cus:3d} CUs: {med * 1e3:7.1f} us  {nbytes / 1e6:7.1f} MB moved  {nbytes / med / 1e6:6.0f} GB/s", flush=True)
+    # RoPE inside the prefill step (`rope` on the batch: keys rotated on their way into the pages) against the
+    # rotation as a pass of its own before the step: wall time per step, 4 x 2048 tokens, page write included
+    import math
+    import time
+    import workloads as W
+    L = W.get_config("c2").layer
+    ctx.set_kernel_timing(False)
+    num_pages = 4096
+    nbytes = S.pool_bytes(S.SPD_KV_GQA, L.page_tokens, L.n_kv_heads, L.dim_qk, L.dim_v, num_pages)
+    mem = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    pool = S.Pool(ctx, mem, nbytes, S.SPD_KV_GQA, L.page_tokens, L.n_kv_heads, L.dim_qk, L.dim_v, num_pages)
+    lens = [2048] * 4
+    T = sum(lens)
+    cu = [0, 2048, 4096, 6144, 8192]
+    pos = [i % 2048 for i in range(T)]
+    q = torch.randn((T, HQ, D), device=dev, dtype=torch.bfloat16)
+    k = torch.randn((T, HKV, D), device=dev, dtype=torch.bfloat16)
+    v = torch.randn((T, HKV, D), device=dev, dtype=torch.bfloat16)
+    out = torch.empty_like(q)
+    scale = 1.0 / math.sqrt(D)
+    plain = pool.make_prefill_batch([1, 2, 3, 4], cu, q, k, v, out, HQ, HKV, D, D, scale)
+    inside = pool.make_prefill_batch([1, 2, 3, 4], cu, q, k, v, out, HQ, HKV, D, D, scale, rope=cfg)
+    for split in ((total // 2, total // 2), (total, total)):
+        ctx.set_partition(*split)
+        row = []
+        for name, fn in (("no RoPE", lambda: pool.prefill_step_batch(plain)),
+                         ("RoPE pass + step", lambda: (ctx.rope_qk(PRE, cfg, pos, q, HQ, k, HKV, D), pool.prefill_step_batch(plain))),
+                         ("RoPE inside the step", lambda: pool.prefill_step_batch(inside))):
+            for _ in range(5):
+                fn()
+            ctx.phase_sync(PRE)
+            t0 = time.perf_counter()
+            for _ in range(40):
+                fn()
+            ctx.phase_sync(PRE)
+            row.append(f"{name} {(time.perf_counter() - t0) / 40 * 1e6:6.1f} us")
+        print(f"prefill step 4 x 2048 on {split[0]:3d} CUs: " + ", ".join(row), flush=True)
+    pool.close()
     ctx.close()
 
 

@@ -66,7 +66,7 @@ class spd_prefill_batch(C.Structure):
                 ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p), ("latent", C.c_void_p),
                 ("out", C.c_void_p), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("dim_qk", C.c_int32), ("dim_v", C.c_int32), ("scale", C.c_float),
-                ("prefix_lens", C.POINTER(C.c_int32))]
+                ("prefix_lens", C.POINTER(C.c_int32)), ("rope", C.POINTER(spd_rope_config))]
 
 
 class spd_decode_batch(C.Structure):
@@ -391,20 +391,23 @@ class Pool:
                "spd_kv_gather")
 
     def prefill_step(self, req_ids: Sequence[int], cu_seqlens: Sequence[int], q, k, v, out, n_q_heads: int,
-                     n_kv_heads: int, dim_qk: int, dim_v: int, scale: float, latent=None, prefix_lens=None) -> None:
+                     n_kv_heads: int, dim_qk: int, dim_v: int, scale: float, latent=None, prefix_lens=None,
+                     rope: Optional[spd_rope_config] = None) -> None:
         self.prefill_step_batch(self.make_prefill_batch(req_ids, cu_seqlens, q, k, v, out, n_q_heads, n_kv_heads,
-                                                        dim_qk, dim_v, scale, latent, prefix_lens))
+                                                        dim_qk, dim_v, scale, latent, prefix_lens, rope))
 
     def make_prefill_batch(self, req_ids: Sequence[int], cu_seqlens: Sequence[int], q, k, v, out, n_q_heads: int,
-                           n_kv_heads: int, dim_qk: int, dim_v: int, scale: float, latent=None, prefix_lens=None):
+                           n_kv_heads: int, dim_qk: int, dim_v: int, scale: float, latent=None, prefix_lens=None,
+                           rope: Optional[spd_rope_config] = None):
         """Marshal once; the returned object can be passed to prefill_step_batch repeatedly."""
         n = len(req_ids)
         ids = (C.c_uint64 * n)(*req_ids)
         cu = (C.c_int32 * (n + 1))(*[int(x) for x in cu_seqlens])
         pre = (C.c_int32 * n)(*[int(x) for x in prefix_lens]) if prefix_lens is not None else None
+        rp = C.pointer(rope) if rope is not None else None
         b = spd_prefill_batch(n, ids, cu, _ptr(q), _ptr(k), _ptr(v), _ptr(latent), _ptr(out), n_q_heads,
-                              n_kv_heads, dim_qk, dim_v, scale, pre)
-        b._keep = (ids, cu, q, k, v, out, latent, pre)
+                              n_kv_heads, dim_qk, dim_v, scale, pre, rp)
+        b._keep = (ids, cu, q, k, v, out, latent, pre, rope, rp)
         return b
 
     def prefill_step_batch(self, batch) -> None:

@@ -144,6 +144,87 @@ def test_rope_then_prefill_step_end_to_end():
     _assert_rope(kg, R.apply_rope(f64(k), pos, o)[:lens[0]], _pair_magnitude(f64(k), o, 0)[:lens[0]], "rotated keys in the pages")
 
 
+# ----------------------------------------------------------------------------- inside the prefill step
+FUSED_CASES = [
+    # name, layer, oracle config, offset, prompt lengths, cached prefix per request (None: plain prefill)
+    ("llama31 128 dims", W.LayerShape("gqa", 8, 2, 128, 128, 16), R.LLAMA31, 0, (37, 150, 16), None),
+    ("64 dims, 8 KV heads", W.LayerShape("gqa", 8, 8, 64, 64, 16), R.RopeConfig(theta=10000.0, rotary_dim=64), 0, (70, 1, 33), None),
+    ("interleaved part of the head", W.LayerShape("gqa", 4, 2, 128, 128, 16),
+     R.RopeConfig(theta=10000.0, rotary_dim=32, interleaved=True), 64, (45, 90), None),
+    ("half layout, part of the head", W.LayerShape("gqa", 4, 4, 128, 128, 16), R.RopeConfig(theta=10000.0, rotary_dim=64), 32, (100,), None),
+    ("piece of a prompt over a cached prefix", W.LayerShape("gqa", 8, 2, 128, 128, 16), R.LLAMA31, 0, (40, 21), (27, 100)),
+    ("one KV head: no fused form, same result", W.LayerShape("gqa", 4, 1, 128, 128, 16), R.LLAMA31, 0, (50, 19), None),
+]
+
+
+@pytest.mark.parametrize("name,L,o,offset,lens,prefix", FUSED_CASES, ids=[c[0] for c in FUSED_CASES])
+def test_prefill_step_with_rope_inside(name, L, o, offset, lens, prefix):
+    """`rope` on the prefill batch: the step rotates q and k itself (the keys on their way into the pages).  Bit for
+    bit what spd_rope_qk followed by the plain step gives (same arithmetic), and the oracle's rotation + attention."""
+    rng = np.random.default_rng(len(name))
+    q, k, v, cu = W.prefill_inputs(L, lens, seed=90 + len(name))
+    scale = 1.0 / np.sqrt(L.dim_qk)
+    cfg = _lib_cfg(o, offset)
+    pre = list(prefix) if prefix else [0] * len(lens)
+    pos = np.concatenate([p0 + np.arange(n) for p0, n in zip(pre, lens)])
+    ids = list(range(1, len(lens) + 1))
+    # cached prefixes: rotated keys already in the pages (written through the unfused path)
+    cached = []
+    results = []
+    for fused in (True, False):
+        gp = GpuPool(L, 64, poison=True)
+        for r, p0 in zip(ids, pre):
+            if p0:
+                kc = W.normal_bf16(np.random.default_rng(1000 + r), (p0, L.n_kv_heads, L.dim_qk))
+                vc = W.normal_bf16(np.random.default_rng(2000 + r), (p0, L.n_kv_heads, L.dim_v))
+                tkc = dev_bf16(kc)
+                gp.ctx.rope_qk(PRE, cfg, list(range(p0)), None, 0, tkc, L.n_kv_heads, L.dim_qk)
+                gp.pool.kv_reserve(r, p0)
+                gp.pool.kv_write(PRE, r, 0, p0, tkc, dev_bf16(vc))
+                if fused:
+                    cached.append((kc, vc))
+        tq, tk, tv = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+        out = torch.zeros((q.shape[0], L.n_q_heads, L.dim_v), dtype=torch.bfloat16, device=DEV)
+        if fused:
+            gp.pool.prefill_step(ids, cu, tq, tk, tv, out, L.n_q_heads, L.n_kv_heads, L.dim_qk, L.dim_v, scale,
+                                 prefix_lens=prefix, rope=cfg)
+        else:
+            gp.ctx.rope_qk(PRE, cfg, [int(p) for p in pos], tq, L.n_q_heads, tk, L.n_kv_heads, L.dim_qk)
+            gp.pool.prefill_step(ids, cu, tq, tk, tv, out, L.n_q_heads, L.n_kv_heads, L.dim_qk, L.dim_v, scale, prefix_lens=prefix)
+        pages = []
+        for r, p0, n in zip(ids, pre, lens):
+            kg = torch.zeros((p0 + n, L.n_kv_heads, L.dim_qk), dtype=torch.bfloat16, device=DEV)
+            vg = torch.zeros((p0 + n, L.n_kv_heads, L.dim_v), dtype=torch.bfloat16, device=DEV)
+            gp.pool.kv_gather(PRE, r, p0 + n, kg, vg)
+            pages.append((kg, vg))
+        gp.ctx.phase_sync(PRE)
+        from gpu_util import host_bits
+        results.append((host_bits(out), host_bits(tq), host_bits(tk), [(host_bits(a), host_bits(b)) for a, b in pages]))
+        gp.close()
+    (out_f, q_f, k_f, pages_f), (out_u, q_u, k_u, pages_u) = results
+    np.testing.assert_array_equal(q_f, q_u)           # q and k rotated in place, as by spd_rope_qk
+    np.testing.assert_array_equal(k_f, k_u)
+    for (ka, va), (kb, vb) in zip(pages_f, pages_u):
+        np.testing.assert_array_equal(ka, kb)
+        np.testing.assert_array_equal(va, vb)
+    np.testing.assert_array_equal(out_f, out_u)
+    # against the oracle: rotation in fp64, rounded to bf16 (what the pages and the attention hold), then attention
+    q_rot = f64(W.to_bf16_bits(_oracle(f64(q), pos, o, offset)))
+    k_rot = f64(W.to_bf16_bits(_oracle(f64(k), pos, o, offset)))
+    _assert_rope(f64(k_f), _oracle(f64(k), pos, o, offset), _pair_magnitude(f64(k), o, offset), "keys rotated by the step")
+    for i, (r, p0, n) in enumerate(zip(ids, pre, lens)):
+        a, b = cu[i], cu[i + 1]
+        if p0:
+            kc, vc = cached[i]
+            kc_rot = f64(W.to_bf16_bits(_oracle(f64(kc), np.arange(p0), o, offset)))
+            kk = np.concatenate([kc_rot, k_rot[a:b]])
+            vv = np.concatenate([f64(vc), f64(v[a:b])])
+            want = OA.chunk_attention(q_rot[a:b], kk, vv, scale)
+        else:
+            want = OA.causal_attention(q_rot[a:b], k_rot[a:b], f64(v[a:b]), scale)
+        assert_parity(f64(out_f)[a:b], want, f"{name}: request {r}")
+
+
 # ----------------------------------------------------------------------------- fused into the decode step
 def _round_bf16(x64: np.ndarray) -> np.ndarray:
     return f64(W.to_bf16_bits(x64))
