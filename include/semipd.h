@@ -136,6 +136,33 @@ int spd_kv_write(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int32
 int spd_kv_gather(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int32_t n_tokens,
                   void* k_out, void* v_out);
 
+/* ------------------------------------------------------------------ the allocator across processes
+ * Paper, "Unified Memory Manager" and "Computational Resource Controller": the two workers are two
+ * PROCESSES over one KV cache that a resident process keeps; an allocation is atomic across them.  The
+ * calls below keep the allocator state itself - free stack, block tables, utilisation, operation
+ * numbers - in a POSIX shared-memory segment `name` (must start with '/') under a process-shared
+ * mutex inside the segment, so that every worker process that opens the segment allocates from the
+ * same pool with the same policy and results as spd_kv_reserve / spd_kv_free above (free list a stack
+ * whose first pops are 0, 1, 2, ...; all-or-nothing; blocks returned last to first; one operation
+ * number per successful mutating call, in the order the calls took the lock).  Host logic only: no GPU
+ * is touched, the pages themselves are not part of the segment.  At most max_requests requests are
+ * live at a time (SPD_ENOMEM beyond, nothing changes).  create fails with SPD_ESTATE if the name
+ * exists; open with SPD_ENOENT if it does not, SPD_ESTATE if it is not a complete pool segment.
+ * close unmaps (the segment lives on); unlink removes the name.  If a process dies inside a call
+ * the next caller finds the lock abandoned and every later call returns SPD_ESTATE: the state can no
+ * longer be trusted. */
+typedef struct spd_shm_pool spd_shm_pool;
+int spd_shm_pool_create(const char* name, int64_t num_pages, int32_t page_tokens, int32_t max_requests,
+                        spd_shm_pool** out);
+int spd_shm_pool_open(const char* name, spd_shm_pool** out);
+int spd_shm_pool_close(spd_shm_pool* pool);
+int spd_shm_pool_unlink(const char* name);
+int spd_shm_pool_stats(spd_shm_pool* pool, int64_t* total, int64_t* free_pages, int64_t* live_reqs, uint64_t* op_seq);
+int spd_shm_kv_reserve(spd_shm_pool* pool, uint64_t req_id, int32_t n_tokens_total, uint64_t* op_seq_out);
+int spd_shm_kv_free(spd_shm_pool* pool, uint64_t req_id, uint64_t* op_seq_out);
+int spd_shm_kv_block_table(spd_shm_pool* pool, uint64_t req_id, int32_t* out, int32_t cap, int32_t* n_out);
+int spd_shm_kv_free_list(spd_shm_pool* pool, int32_t* out, int64_t cap, int64_t* n_out);
+
 /* ------------------------------------------------------------------ the two steps */
 
 /* Prefill step (paper, Background "LLM Processing Phases" and "Prefill and Decode

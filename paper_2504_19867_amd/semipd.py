@@ -32,6 +32,8 @@ EXPORTS = [
     "spd_ctrl_create", "spd_ctrl_destroy", "spd_ctrl_observe_ttft", "spd_ctrl_observe_tpot", "spd_ctrl_step", "spd_ctrl_model",
     "spd_rope_inv_freq", "spd_rope_qk", "spd_ffn_gate_up", "spd_ffn_pack_gate_up",
     "spd_decode_step_noalloc", "spd_noalloc_limits", "spd_phase_read", "spd_clock_probe",
+    "spd_shm_pool_create", "spd_shm_pool_open", "spd_shm_pool_close", "spd_shm_pool_unlink", "spd_shm_pool_stats",
+    "spd_shm_kv_reserve", "spd_shm_kv_free", "spd_shm_kv_block_table", "spd_shm_kv_free_list",
 ]
 
 
@@ -132,6 +134,15 @@ def _load() -> C.CDLL:
         "spd_rope_qk": [vp, C.c_int, P(spd_rope_config), P(i32), i32, vp, i32, vp, i32, i32],
         "spd_ffn_gate_up": [vp, C.c_int, vp, vp, vp, i32, i32, i32],
         "spd_ffn_pack_gate_up": [vp, C.c_int, vp, vp, vp, i32, i32],
+        "spd_shm_pool_create": [C.c_char_p, i64, i32, i32, P(vp)],
+        "spd_shm_pool_open": [C.c_char_p, P(vp)],
+        "spd_shm_pool_close": [vp],
+        "spd_shm_pool_unlink": [C.c_char_p],
+        "spd_shm_pool_stats": [vp, P(i64), P(i64), P(i64), P(u64)],
+        "spd_shm_kv_reserve": [vp, u64, i32, P(u64)],
+        "spd_shm_kv_free": [vp, u64, P(u64)],
+        "spd_shm_kv_block_table": [vp, u64, P(i32), i32, P(i32)],
+        "spd_shm_kv_free_list": [vp, P(i32), i64, P(i64)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -330,6 +341,59 @@ def pool_bytes(kind: int, page_tokens: int, n_kv_heads: int, dim_k: int, dim_v: 
     out = C.c_uint64()
     _check(lib.spd_pool_bytes(C.byref(desc), C.byref(out)), "spd_pool_bytes")
     return out.value
+
+
+class ShmPool:
+    """The allocator in POSIX shared memory (spd_shm_*): marshalling only.  `create=True` makes the segment,
+    otherwise an existing one is opened (by another process, say)."""
+
+    def __init__(self, name: str, num_pages: int = 0, page_tokens: int = 0, max_requests: int = 0, create: bool = False):
+        h = C.c_void_p()
+        self.name = name.encode()
+        if create:
+            _check(lib.spd_shm_pool_create(self.name, num_pages, page_tokens, max_requests, C.byref(h)), "spd_shm_pool_create")
+        else:
+            _check(lib.spd_shm_pool_open(self.name, C.byref(h)), "spd_shm_pool_open")
+        self.h = h
+
+    def close(self) -> None:
+        if self.h:
+            _check(lib.spd_shm_pool_close(self.h), "spd_shm_pool_close")
+            self.h = None
+
+    def unlink(self) -> None:
+        _check(lib.spd_shm_pool_unlink(self.name), "spd_shm_pool_unlink")
+
+    def stats(self) -> Tuple[int, int, int, int]:
+        t, f, l, s = C.c_int64(), C.c_int64(), C.c_int64(), C.c_uint64()
+        _check(lib.spd_shm_pool_stats(self.h, C.byref(t), C.byref(f), C.byref(l), C.byref(s)), "spd_shm_pool_stats")
+        return t.value, f.value, l.value, s.value
+
+    def kv_reserve(self, req_id: int, n_tokens_total: int) -> int:
+        seq = C.c_uint64()
+        _check(lib.spd_shm_kv_reserve(self.h, req_id, n_tokens_total, C.byref(seq)), "spd_shm_kv_reserve")
+        return seq.value
+
+    def kv_free(self, req_id: int) -> int:
+        seq = C.c_uint64()
+        _check(lib.spd_shm_kv_free(self.h, req_id, C.byref(seq)), "spd_shm_kv_free")
+        return seq.value
+
+    def kv_block_table(self, req_id: int) -> List[int]:
+        n = C.c_int32()
+        rc = lib.spd_shm_kv_block_table(self.h, req_id, None, 0, C.byref(n))
+        if rc not in (SPD_OK, SPD_EINVAL):
+            _check(rc, "spd_shm_kv_block_table")
+        buf = (C.c_int32 * max(n.value, 1))()
+        _check(lib.spd_shm_kv_block_table(self.h, req_id, buf, n.value, C.byref(n)), "spd_shm_kv_block_table")
+        return [int(buf[i]) for i in range(n.value)]
+
+    def kv_free_list(self) -> List[int]:
+        n = C.c_int64()
+        lib.spd_shm_kv_free_list(self.h, None, 0, C.byref(n))
+        buf = (C.c_int32 * max(n.value, 1))()
+        _check(lib.spd_shm_kv_free_list(self.h, buf, n.value, C.byref(n)), "spd_shm_kv_free_list")
+        return [int(buf[i]) for i in range(n.value)]
 
 
 class Pool:
