@@ -73,7 +73,7 @@ def median(xs):
 
 
 class Bench:
-    def __init__(self, cfg, pool_gb=None, scramble=True):
+    def __init__(self, cfg, pool_gb=None, scramble=True, fp8=False):
         import torch
         from paper_2504_19867_amd import semipd as S
         self.torch, self.S, self.cfg = torch, S, cfg
@@ -85,8 +85,11 @@ class Bench:
         num_pages = cfg.num_pages if pool_gb is None else int(pool_gb * 1e9) // L.page_bytes
         self.num_pages = num_pages
         mla = L.kind == "mla"
-        kind = S.SPD_KV_MLA_LATENT if mla else S.SPD_KV_GQA
+        assert mla or not fp8, "the FP8 cache is the latent path's"
+        kind = (S.SPD_KV_MLA_LATENT_FP8 if fp8 else S.SPD_KV_MLA_LATENT) if mla else S.SPD_KV_GQA
         pk, pv = (L.latent_dim, L.latent_v_dim) if mla else (L.dim_qk, L.dim_v)
+        if fp8 and pool_gb is None:
+            num_pages = self.num_pages = 40_000_000_000 // (L.page_tokens * 656)      # the same 40 GB hold 1.76 x the tokens
         nbytes = S.pool_bytes(kind, L.page_tokens, L.n_kv_heads, pk, pv, num_pages)
         self.mem = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
         self.pool = S.Pool(self.ctx, self.mem, nbytes, kind, L.page_tokens, L.n_kv_heads, pk, pv, num_pages)
@@ -148,7 +151,7 @@ class Bench:
         G = L.n_q_heads
         self.prefill_flops = sum(2.0 * (L.dim_qk + L.dim_v) * G * n * (n + 1) / 2 for n in cfg.prefill_lens)
         if mla:
-            kv_bytes = sum(cfg.decode_ctx) * L.latent_dim * 2
+            kv_bytes = sum(cfg.decode_ctx) * (656 if fp8 else L.latent_dim * 2)      # FP8 rows: 512 codes + 4 scales + 64 bf16
             qo_bytes = self.B * L.n_q_heads * (L.latent_dim + L.latent_v_dim) * 2
         else:
             kv_bytes = sum(cfg.decode_ctx) * L.n_kv_heads * (L.dim_qk + L.dim_v) * 2
@@ -397,10 +400,10 @@ def cpu_baseline(cfg, r):
             "prefill_tok_s": sum(cfg.prefill_lens) / t_p, "decode_tok_s": len(cfg.decode_ctx) / t_d}
 
 
-def measure_config(cfg, args, steps, warmup, sweep, clock):
+def measure_config(cfg, args, steps, warmup, sweep, clock, fp8=False):
     """All figures of one workload: the headline split (solo passes, then the two asynchronous workers), optionally
     the split sweep and the clock probe; returns the workload's part of the JSON line."""
-    bench = Bench(cfg, args.pool_gb, not args.no_scramble)
+    bench = Bench(cfg, args.pool_gb, not args.no_scramble, fp8)
     p_pct, d_pct = (int(x) for x in args.split.split("/"))
 
     def measure_split(pp, dp, steps, warmup, only=None):
@@ -458,7 +461,7 @@ def measure_config(cfg, args, steps, warmup, sweep, clock):
 
     r = head["decode_per_prefill"]
     tokens_per_step = (bench.T if args.only != "decode" else 0) + (r * bench.B if args.only != "prefill" else 0)
-    traffic_p, traffic_d = profiled_traffic(cfg.name)
+    traffic_p, traffic_d = profiled_traffic(cfg.name + ("_fp8kv" if fp8 else ""))
     L = cfg.layer
     part = {
         "value": tokens_per_step / head["ms_per_step"] * 1e3,
@@ -479,7 +482,7 @@ def measure_config(cfg, args, steps, warmup, sweep, clock):
                      "kernel_ms": head["prefill_kernel_ms"], "flops_per_launch": bench.prefill_flops,
                      "share_cus": head["prefill_cus"],
                      "frac_of_share_peak": (head["prefill_tflops"] or 0.0) / (PEAK_BF16_TFLOPS * head["prefill_cus"] / bench.total_cus)},
-        "roofline_decode": {"bound": "hbm", "kernel": ("decode_mla_kernel" if L.kind == "mla" else f"decode_gqa_kernel<{L.dim_qk}>") + " (+combine)", "achieved": head["decode_gbs"],
+        "roofline_decode": {"bound": "hbm", "kernel": (("decode_mla_kernel<fp8 pages>" if fp8 else "decode_mla_kernel") if L.kind == "mla" else f"decode_gqa_kernel<{L.dim_qk}>") + " (+combine)", "achieved": head["decode_gbs"],
                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": (head["decode_gbs"] or 0.0) / PEAK_HBM_GBS,
                             "traffic": traffic_d, "traffic_source": "profiles/hbm_traffic_pmc.md" if traffic_d else None,
                             "kernel_ms": head["decode_kernel_ms"],
@@ -526,6 +529,13 @@ def main():
             sub["steps"] = steps
             sub["unit"] = result["unit"]
             result["configs"][other.name] = sub
+            if other.layer.kind == "mla":
+                # the same workload over the FP8 latent cache (656 instead of 1152 bytes per cached token)
+                sub8, _ = measure_config(other, args, steps, 2, False, False, fp8=True)
+                sub8["steps"] = steps
+                sub8["unit"] = result["unit"]
+                sub8["config"]["kv_cache"] = "fp8 e4m3, one fp32 scale per 128 latent entries, rope entries bf16"
+                result["configs"][other.name + "_fp8kv"] = sub8
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cfg, r)
     print(json.dumps(result))

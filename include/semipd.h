@@ -50,7 +50,7 @@ enum {
 
 enum { SPD_PHASE_PREFILL = 0, SPD_PHASE_DECODE = 1 };
 
-typedef enum { SPD_KV_GQA = 0, SPD_KV_MLA_LATENT = 1 } spd_kv_kind;
+typedef enum { SPD_KV_GQA = 0, SPD_KV_MLA_LATENT = 1, SPD_KV_MLA_LATENT_FP8 = 2 } spd_kv_kind;
 
 /* ------------------------------------------------------------------ context */
 
@@ -77,7 +77,16 @@ int spd_device_info(spd_ctx* ctx, int* total_cus, int* xcds, int* cu_granularity
  * Page geometry.  GQA: a page holds page_tokens tokens of K [n_kv_heads, dim_k] and
  * V [n_kv_heads, dim_v]; page_tokens must be a multiple of 16; dim_k == dim_v in {64, 128}.
  * MLA latent: a page holds page_tokens rows of dim_k (= 576) values, n_kv_heads = 1,
- * dim_v = 512 is the number of leading dims that act as values; page_tokens % 16 == 0.
+ * dim_v = 512 is the number of leading dims that act as values; page_tokens % 32 == 0.
+ * MLA latent, FP8 (paper, Evaluation "Model": DeepSeek-V3 is served with FP8 precision; the format is
+ * this library's reading): the same geometry, but a cached row keeps its 512 leading entries as OCP
+ * FP8 E4M3 codes with one fp32 scale per block of 128 entries (scale = largest magnitude of the block
+ * / 448, or 1 for an all-zero block; code = E4M3(clamp(x / scale, -448, 448)), nearest even, division
+ * and scale in fp32) and its 64 rope entries in bf16: 656 bytes per token instead of 1152.  Every call
+ * takes and returns the same bf16 tensors as for a bf16 latent pool: rows are quantised on their way
+ * into the pages, spd_kv_gather hands back decode(code) * scale rounded to bf16, and the decode step
+ * attends over exactly those dequantised rows.  RoPE inside the decode step is not offered on such a
+ * pool (SPD_EINVAL).
  * The byte layout inside a page is private to the library (it is arranged for the
  * decode kernel's matrix-core operand order); read or write pages only through
  * spd_kv_write / spd_kv_gather / the steps. */

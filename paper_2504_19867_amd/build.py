@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsemipd.so")
-SOURCES = ["pool.cpp", "ctx.cpp", "steps.cpp", "controller.cpp", "kernels_kv.hip", "kernels_decode.hip", "kernels_decode_mla.hip",
+SOURCES = ["pool.cpp", "ctx.cpp", "steps.cpp", "controller.cpp", "kernels_kv.hip", "kernels_kv_fp8.hip", "kernels_decode.hip", "kernels_decode_mla.hip",
            "kernels_prefill.hip", "kernels_rope.hip", "rope.cpp", "kernels_ffn.hip", "ffn.cpp", "noalloc.hip", "shm_pool.cpp"]
 # packed fp32 VALU forms are switched off for all device code
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

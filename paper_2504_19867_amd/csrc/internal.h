@@ -34,6 +34,8 @@ namespace spd {
 // through LDS and reads them back in both operand orders (kernels_decode_mla.hip).
 // ---------------------------------------------------------------------------------------------
 constexpr int TILE_T = 16;
+// FP8 latent pages: a cached row is 512 E4M3 codes, 4 fp32 scales (one per 128 entries) and 64 bf16 rope entries
+constexpr int FP8_ROW_BYTES = 512 + 16 + 128;
 
 struct PoolGeom {
   int kind, P, Hkv, dk, dv;
@@ -51,7 +53,7 @@ inline PoolGeom make_geom(const spd_pool_desc& d) {
   PoolGeom g{};
   g.kind = d.kind; g.P = d.page_tokens; g.Hkv = d.n_kv_heads; g.dk = d.dim_k; g.dv = d.dim_v;
   g.tiles_per_page = d.page_tokens / TILE_T;
-  g.tile_k_bytes = TILE_T * d.dim_k * 2;
+  g.tile_k_bytes = d.kind == SPD_KV_MLA_LATENT_FP8 ? TILE_T * FP8_ROW_BYTES : TILE_T * d.dim_k * 2;
   g.tile_v_bytes = d.kind == SPD_KV_GQA ? TILE_T * d.dim_v * 2 : 0;
   g.tile_bytes = g.tile_k_bytes + g.tile_v_bytes;
   g.head_bytes = g.tiles_per_page * g.tile_bytes;
@@ -189,6 +191,13 @@ hipError_t launch_kv_write(const PoolGeom& g, char* pool_base, const TileDesc* d
 bool kv_write_can_rotate(const PoolGeom& g);
 hipError_t launch_kv_gather(const PoolGeom& g, const char* pool_base, const TileDesc* d_tiles, int n_tiles,
                             void* k_out, void* v_out, hipStream_t stream);
+// FP8 latent pools (kernels_kv_fp8.hip): quantising page write of dense [rows, 576] bf16 latent rows (with the same
+// optional metadata copy as launch_kv_write), and the gather that hands back the dequantised rows
+hipError_t launch_kv_write_fp8(const PoolGeom& g, char* pool_base, const TileDesc* d_tiles, int n_tiles, const void* latent,
+                               hipStream_t stream, void* copy_dst = nullptr, const void* copy_src = nullptr,
+                               uint64_t copy_bytes = 0);
+hipError_t launch_kv_gather_fp8(const PoolGeom& g, const char* pool_base, const TileDesc* d_tiles, int n_tiles, void* out,
+                                hipStream_t stream);
 hipError_t launch_decode_gqa(const PoolGeom& g, const char* pool_base, const void* q, void* out,
                              const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride,
                              const void* d_items, int n_items, int B, int H, float scale, int chunk_tiles,
@@ -196,7 +205,7 @@ hipError_t launch_decode_gqa(const PoolGeom& g, const char* pool_base, const voi
 hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const void* q, void* out,
                              const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride,
                              const void* d_items, int n_items, int B, int H, float scale, int chunk_steps,
-                             int max_chunks, float* ws_o, float* ws_ml, hipStream_t stream);
+                             int max_chunks, float* ws_o, float* ws_ml, hipStream_t stream, bool fp8 = false);
 int decode_mla_step_tokens();
 // one workgroup per chain: workgroup b computes the items d_work[d_chain[b]] .. d_work[d_chain[b + 1] - 1]
 hipError_t launch_prefill(const void* q, const void* k, const void* v, void* out, const PrefillWork* d_work,

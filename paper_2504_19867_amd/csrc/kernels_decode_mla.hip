@@ -81,6 +81,11 @@ __device__ inline float mla_max_over_rows(float x) {
 #define SPD_MLA_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (0 << 8) | (((N) >> 4) << 14))
 
 // grid (n_items), block 256: work item = (request, chunk).  chunk_steps = 16-token steps per chunk.
+// FP8: the pages hold 656-byte rows (512 E4M3 codes, 4 fp32 scales, 64 bf16 rope entries; kernels_kv_fp8.hip).  Such
+// rows cannot go to LDS as they are: a step's rows travel through registers instead (16-byte pieces, two steps'
+// worth in flight per lane), are multiplied out to bf16 (decode(code) * scale, rounded once) and stored into the
+// stage in the very layout the bf16 path loads, so everything after the stage is shared.
+template <bool FP8>
 __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
     const char* __restrict__ pool, uint64_t page_bytes, int steps_per_page, const bf16_t* __restrict__ q,
     bf16_t* __restrict__ out, const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ bt, int bt_stride,
@@ -160,9 +165,64 @@ __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
   for (int i = 0; i < VB; ++i) O[i] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m = -INFINITY, l = 0.f;
 
+  // ---- FP8 rows: piece q = thread + 256 j (j < 3) of a step's 16 x 41 16-byte pieces; piece pc of a row is 16 codes
+  // (pc < 32), the scales (pc = 32, fetched word by word with the codes they belong to) or 8 rope entries (pc > 32)
+  constexpr int FP8_PIECES = FP8_ROW_BYTES / 16;             // 41
+  constexpr int FP8_STEP_BYTES = STEP_T * FP8_ROW_BYTES;     // 10496
+  struct Fp8Regs { uint4 d[3]; float sc[3]; };
+  auto fp8_load = [&](const char* src, Fp8Regs& r) {
 #pragma unroll
-  for (int t = 0; t < PD; ++t)
-    if (t < n_steps) issue_loads(t);
+    for (int j = 0; j < 3; ++j) {
+      const int qd = (int)threadIdx.x + 256 * j, row = qd / FP8_PIECES, pc = qd % FP8_PIECES;
+      r.d[j] = uint4{0, 0, 0, 0};
+      r.sc[j] = 0.f;
+      if (qd < STEP_T * FP8_PIECES && pc != 32) {
+        r.d[j] = *(const uint4*)(src + row * FP8_ROW_BYTES + pc * 16);
+        if (pc < 32) r.sc[j] = *(const float*)(src + row * FP8_ROW_BYTES + 512 + 4 * (pc >> 3));
+      }
+    }
+  };
+  auto fp8_store = [&](int st, const Fp8Regs& r) {
+    char* stage = smem + (st % NSTAGE) * STAGE_BYTES;
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const int qd = (int)threadIdx.x + 256 * j, row = qd / FP8_PIECES, pc = qd % FP8_PIECES;
+      if (qd >= STEP_T * FP8_PIECES || pc == 32) continue;
+      char* lrow = stage + row * ROW_BYTES;
+      if (pc > 32) {                                         // rope entries: chunk 64 + (pc - 33), as they are
+        *(uint4*)(lrow + (((64 + pc - 33) ^ (row & 7)) * 16)) = r.d[j];
+      } else {                                               // 16 codes -> chunks 2 pc and 2 pc + 1
+        const uint32_t cw[4] = {r.d[j].x, r.d[j].y, r.d[j].z, r.d[j].w};
+        uint32_t o[8];
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4) {
+          const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)cw[k4], false), bb = __builtin_amdgcn_cvt_pk_f32_fp8((int)cw[k4], true);
+          o[2 * k4] = mla_pack_bf16(a[0] * r.sc[j], a[1] * r.sc[j]);
+          o[2 * k4 + 1] = mla_pack_bf16(bb[0] * r.sc[j], bb[1] * r.sc[j]);
+        }
+        *(uint4*)(lrow + (((2 * pc) ^ (row & 7)) * 16)) = uint4{o[0], o[1], o[2], o[3]};
+        *(uint4*)(lrow + (((2 * pc + 1) ^ (row & 7)) * 16)) = uint4{o[4], o[5], o[6], o[7]};
+      }
+    }
+  };
+  auto fp8_src = [&](int st) -> const char* {
+    const int gs = step0 + st;
+    const int page = bt_row[gs / steps_per_page];
+    return pool + (uint64_t)page * page_bytes + (size_t)(gs % steps_per_page) * FP8_STEP_BYTES;
+  };
+  Fp8Regs set_a, set_b;                                      // set_a: the step stored next; set_b: the one after
+  if constexpr (FP8) {
+    // steps 0 and 1 on their way, step 0 into its stage, step 2 behind it
+    fp8_load(fp8_src(0), set_a);
+    if (n_steps > 1) fp8_load(fp8_src(1), set_b);
+    fp8_store(0, set_a);
+    set_a = set_b;
+    if (n_steps > 2) fp8_load(fp8_src(2), set_b);
+  } else {
+#pragma unroll
+    for (int t = 0; t < PD; ++t)
+      if (t < n_steps) issue_loads(t);
+  }
   // The loop itself touches neither the block table in memory nor a division: lane i of `pages` holds the id of
   // the chunk's i-th page, the step to load next is tracked as (page, step inside the page).
   const int page_first = step0 / steps_per_page;
@@ -185,7 +245,9 @@ __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
   for (int st = 0; st < n_steps; ++st) {
     // this wave's loads of step st are done when at most (steps issued after it) * (its loads per step) remain
     const int later = min(PD - 1, n_steps - 1 - st);
-    if (five) {
+    if constexpr (FP8) {
+      SPD_MLA_WAIT_VMCNT(63);                      // the register-staged loads are the compiler's to wait for
+    } else if (five) {
       if (later >= 2) SPD_MLA_WAIT_VMCNT(2 * LPW);
       else if (later == 1) SPD_MLA_WAIT_VMCNT(LPW);
       else SPD_MLA_WAIT_VMCNT(0);
@@ -197,10 +259,16 @@ __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
     asm volatile("s_barrier" ::: "memory");        // step st has landed for all waves; stage of st - 1 is free
     const bool more = st + PD < n_steps;
     const int page_next = __builtin_amdgcn_readlane(pages, nl_page & 63);
-    const char* src_next = pool + (uint64_t)page_next * page_bytes + (uint32_t)nl_sub * STAGE_BYTES;
+    const char* src_next = pool + (uint64_t)page_next * page_bytes + (uint32_t)nl_sub * (FP8 ? FP8_STEP_BYTES : STAGE_BYTES);
     if (++nl_sub == steps_per_page) {
       nl_sub = 0;
       ++nl_page;
+    }
+    if constexpr (FP8) {
+      // step st + 1 out of its registers into its stage (free since step st - 3), step st + 3 into the registers
+      if (st + 1 < n_steps) fp8_store(st + 1, set_a);
+      set_a = set_b;
+      if (more) fp8_load(src_next, set_b);
     }
 
     const char* stage = smem + (st % NSTAGE) * STAGE_BYTES;
@@ -233,7 +301,8 @@ __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
     for (int sk = 0; sk < KS; ++sk) {
       acc[sk % 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ring[sk % RING]), qf[sk], acc[sk % 3], 0, 0, 0);
       if (sk + RING < KS) ring[sk % RING] = read_s(sk + RING);
-      if (sk % 3 == 1 && sk / 3 < LPW && more) load_one(src_next, st + PD, sk / 3);
+      if constexpr (!FP8)
+        if (sk % 3 == 1 && sk / 3 < LPW && more) load_one(src_next, st + PD, sk / 3);
       __builtin_amdgcn_sched_barrier(0);
     }
     // value operands: in flight while the vector ALU does the softmax
@@ -334,13 +403,18 @@ int decode_mla_step_tokens() { return mla::STEP_T; }
 hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const void* q, void* out,
                              const int32_t* d_ctx_lens, const int32_t* d_block_tables, int bt_stride,
                              const void* d_items, int n_items, int B, int H, float scale, int chunk_steps,
-                             int max_chunks, float* ws_o, float* ws_ml, hipStream_t stream) {
+                             int max_chunks, float* ws_o, float* ws_ml, hipStream_t stream, bool fp8) {
   const float c = scale * 1.4426950408889634f;
   // the kernel keeps a chunk's page ids in the 64 lanes of one register
   if (chunk_steps <= 0 || (chunk_steps + g.P / mla::STEP_T - 1) / (g.P / mla::STEP_T) + 1 > 64) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(decode_mla_kernel, dim3((unsigned)n_items), dim3(256), 0, stream, pool_base, g.page_bytes,
-                     g.P / mla::STEP_T, (const bf16_t*)q, (bf16_t*)out, d_ctx_lens, d_block_tables, bt_stride,
-                     (const int2*)d_items, H, c, chunk_steps, max_chunks, ws_o, ws_ml);
+  if (fp8)
+    hipLaunchKernelGGL(decode_mla_kernel<true>, dim3((unsigned)n_items), dim3(256), 0, stream, pool_base, g.page_bytes,
+                       g.P / mla::STEP_T, (const bf16_t*)q, (bf16_t*)out, d_ctx_lens, d_block_tables, bt_stride,
+                       (const int2*)d_items, H, c, chunk_steps, max_chunks, ws_o, ws_ml);
+  else
+    hipLaunchKernelGGL(decode_mla_kernel<false>, dim3((unsigned)n_items), dim3(256), 0, stream, pool_base, g.page_bytes,
+                       g.P / mla::STEP_T, (const bf16_t*)q, (bf16_t*)out, d_ctx_lens, d_block_tables, bt_stride,
+                       (const int2*)d_items, H, c, chunk_steps, max_chunks, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || max_chunks <= 1) return e;
   hipLaunchKernelGGL(decode_mla_combine_kernel, dim3(H, B), dim3(512), 0, stream, (bf16_t*)out, d_ctx_lens, H,

@@ -20,7 +20,7 @@ static bool desc_ok(const spd_pool_desc* d) {
     if (d->dim_k != d->dim_v) return false;
     return d->dim_k == 64 || d->dim_k == 128;
   }
-  if (d->kind == SPD_KV_MLA_LATENT)
+  if (d->kind == SPD_KV_MLA_LATENT || d->kind == SPD_KV_MLA_LATENT_FP8)
     return d->n_kv_heads == 1 && d->dim_k == 576 && d->dim_v == 512 && d->page_tokens % 32 == 0;
   return false;
 }

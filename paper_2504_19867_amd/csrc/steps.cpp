@@ -80,8 +80,13 @@ static int kv_copy(spd_ctx* ctx, spd_pool* pool, int phase, uint64_t req_id, int
   if ((rc = stage_acquire(ctx, phase, bytes, &st)) != SPD_OK) return rc;
   memcpy(st->host, descs.data(), bytes);
   if ((rc = stage_copy(st, bytes, stream)) != SPD_OK) return rc;
-  if (write)
+  const bool fp8 = g.kind == SPD_KV_MLA_LATENT_FP8;
+  if (write && fp8)
+    SPD_HIP(launch_kv_write_fp8(g, pool->base, (const TileDesc*)st->dev, (int)descs.size(), k, stream));
+  else if (write)
     SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)st->dev, (int)descs.size(), k, v, stream));
+  else if (fp8)
+    SPD_HIP(launch_kv_gather_fp8(g, pool->base, (const TileDesc*)st->dev, (int)descs.size(), (void*)k, stream));
   else
     SPD_HIP(launch_kv_gather(g, pool->base, (const TileDesc*)st->dev, (int)descs.size(), (void*)k, (void*)v, stream));
   return stage_commit(ctx, phase, st, bytes, stream, false);
@@ -256,10 +261,14 @@ extern "C" int spd_prefill_step(spd_ctx* ctx, spd_pool* pool, const spd_prefill_
     SPD_HIP(launch_rope((void*)b->q, b->n_q_heads, (void*)b->k, b->n_kv_heads, b->dim_qk, rc_->rotary_dim, rc_->rotary_offset,
                         rc_->interleaved != 0, n_rows, (const int32_t*)((const char*)host_dev + off_pos),
                         (const double*)((const char*)host_dev + off_w), stream));
-  SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)((const char*)host_dev + off_desc), (int)descs.size(), page_src_k,
-                          page_src_v, stream, st->dev, host_dev, bytes,
-                          fused ? (const double*)((const char*)host_dev + off_w) : nullptr, fused ? rc_->rotary_dim : 0,
-                          fused ? rc_->rotary_offset : 0, fused && rc_->interleaved != 0));
+  if (g.kind == SPD_KV_MLA_LATENT_FP8)
+    SPD_HIP(launch_kv_write_fp8(g, pool->base, (const TileDesc*)((const char*)host_dev + off_desc), (int)descs.size(), page_src_k,
+                                stream, st->dev, host_dev, bytes));
+  else
+    SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)((const char*)host_dev + off_desc), (int)descs.size(), page_src_k,
+                            page_src_v, stream, st->dev, host_dev, bytes,
+                            fused ? (const double*)((const char*)host_dev + off_w) : nullptr, fused ? rc_->rotary_dim : 0,
+                            fused ? rc_->rotary_offset : 0, fused && rc_->interleaved != 0));
   if (fused)                // the keys were rotated on their way into the pages (and in place); the queries here
     SPD_HIP(launch_rope((void*)b->q, b->n_q_heads, nullptr, 0, b->dim_qk, rc_->rotary_dim, rc_->rotary_offset,
                         rc_->interleaved != 0, n_rows, (const int32_t*)(st->dev + off_pos), (const double*)(st->dev + off_w),
@@ -355,6 +364,7 @@ static int decode_step_impl(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch
         if (b->req_ids[r2] == b->req_ids[r]) return SPD_EINVAL;
   }
   if (b->rope) {
+    if (g.kind == SPD_KV_MLA_LATENT_FP8) return SPD_EINVAL;
     int rrc = rope_config_check(b->rope);
     if (rrc != SPD_OK) return rrc;
     if (b->rope->rotary_dim % 16 || b->rope->rotary_dim > 256 || b->rope->rotary_offset % 8 ||
@@ -364,7 +374,8 @@ static int decode_step_impl(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch
   if (ctx->device < 0) return SPD_ESTATE;
 
   const int B = b->n_req;
-  const bool mla = g.kind == SPD_KV_MLA_LATENT;
+  const bool fp8 = g.kind == SPD_KV_MLA_LATENT_FP8;
+  const bool mla = g.kind == SPD_KV_MLA_LATENT || fp8;
   const int unit_t = mla ? decode_mla_step_tokens() : TILE_T;     // tokens per split-K unit
   int64_t sum_tiles = 0;
   int32_t max_tiles = 0, max_pages = 0;
@@ -474,6 +485,8 @@ static int decode_step_impl(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch
                                b->rope->rotary_dim, b->rope->rotary_offset, b->rope->interleaved != 0,
                                (const double*)(sdev + off_w), stream));
     att_q = ws_q;
+  } else if (append && fp8) {
+    SPD_HIP(launch_kv_write_fp8(g, pool->base, (const TileDesc*)(sdev + off_desc), B, b->k_new, stream));
   } else if (append) {
     SPD_HIP(launch_kv_write(g, pool->base, (const TileDesc*)(sdev + off_desc), B, b->k_new, b->v_new, stream));
   }
@@ -481,7 +494,8 @@ static int decode_step_impl(spd_ctx* ctx, spd_pool* pool, const spd_decode_batch
   if (mla)
     SPD_HIP(launch_decode_mla(g, pool->base, att_q, b->out, (const int32_t*)sdev, (const int32_t*)(sdev + off_bt),
                               bt_stride, sdev + off_items, n_items, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks,
-                              (float*)(max_chunks > 1 ? ws : nullptr), (float*)(max_chunks > 1 ? ws + ws_o_bytes : nullptr), stream));
+                              (float*)(max_chunks > 1 ? ws : nullptr), (float*)(max_chunks > 1 ? ws + ws_o_bytes : nullptr), stream,
+                              fp8));
   else
     SPD_HIP(launch_decode_gqa(g, pool->base, att_q, b->out, (const int32_t*)sdev, (const int32_t*)(sdev + off_bt),
                               bt_stride, sdev + off_items, n_items, B, b->n_q_heads, b->scale, chunk_tiles, max_chunks,

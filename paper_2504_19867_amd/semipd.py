@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("SEMIPD_LIB", os.path.join(_HERE, "libsemipd.so"))   #
 
 SPD_OK, SPD_EINVAL, SPD_ENOMEM, SPD_ENOENT, SPD_EHIP, SPD_ESTATE, SPD_ETOOBIG = 0, -1, -2, -3, -5, -6, -7
 SPD_PHASE_PREFILL, SPD_PHASE_DECODE = 0, 1
-SPD_KV_GQA, SPD_KV_MLA_LATENT = 0, 1
+SPD_KV_GQA, SPD_KV_MLA_LATENT, SPD_KV_MLA_LATENT_FP8 = 0, 1, 2
 
 EXPORTS = [
     "spd_ctx_create", "spd_ctx_destroy", "spd_device_info", "spd_pool_bytes", "spd_pool_create",

@@ -37,9 +37,9 @@ def assert_parity(got: np.ndarray, want: np.ndarray, what: str):
 class GpuPool:
     """A context + pool over a torch-owned byte buffer (optionally pre-filled with NaN patterns)."""
 
-    def __init__(self, layer: W.LayerShape, num_pages: int, poison: bool = False, ctx: S.Context = None):
+    def __init__(self, layer: W.LayerShape, num_pages: int, poison: bool = False, ctx: S.Context = None, kind: int = None):
         self.layer = layer
-        self.kind = S.SPD_KV_GQA if layer.kind == "gqa" else S.SPD_KV_MLA_LATENT
+        self.kind = kind if kind is not None else (S.SPD_KV_GQA if layer.kind == "gqa" else S.SPD_KV_MLA_LATENT)
         self.dim_k = layer.dim_qk if layer.kind == "gqa" else layer.latent_dim
         self.dim_v = layer.dim_v if layer.kind == "gqa" else layer.latent_v_dim
         self.ctx = ctx or S.Context(0)

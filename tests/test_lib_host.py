@@ -176,6 +176,24 @@ def bits(words):
     return {32 * i + b for i, w in enumerate(words) for b in range(32) if (w >> b) & 1}
 
 
+def test_fp8_latent_pool_geometry():
+    """656 bytes per cached token (512 codes, 4 scales, 64 bf16 rope entries) against 1152 for the bf16 latent pool;
+    the same shape rules; the allocator does not care."""
+    assert S.pool_bytes(S.SPD_KV_MLA_LATENT_FP8, 64, 1, 576, 512, 10) == 10 * 64 * 656
+    assert S.pool_bytes(S.SPD_KV_MLA_LATENT, 64, 1, 576, 512, 10) == 10 * 64 * 1152
+    ctx = S.Context(-1)
+    for bad in ((48, 1, 576, 512), (64, 2, 576, 512), (64, 1, 512, 512), (64, 1, 576, 128)):
+        with pytest.raises(S.SpdError) as e:
+            S.Pool(ctx, None, 0, S.SPD_KV_MLA_LATENT_FP8, *bad, 8)
+        assert e.value.status == S.SPD_EINVAL
+    pool = S.Pool(ctx, None, 0, S.SPD_KV_MLA_LATENT_FP8, 64, 1, 576, 512, 8)
+    pool.kv_reserve(1, 130)
+    assert pool.kv_block_table(1) == [0, 1, 2]
+    with pytest.raises(S.SpdError) as e:                       # RoPE inside the decode step is not offered here
+        pool.decode_step([1], [130], 4096, 4096, 16, 1.0, rope=S.rope_config(rotary_dim=64, rotary_offset=512))
+    assert e.value.status == S.SPD_EINVAL
+
+
 @pytest.mark.parametrize("p,d", [(77, 179), (128, 128), (102, 154), (179, 77), (8, 248), (1, 1)])
 def test_partition_masks_disjoint_and_balanced(p, d):
     pm, dm, pr, dr = S.partition_masks(256, 8, p, d)
