@@ -230,6 +230,21 @@ class Bench:
         w, c, _, _ = (int(x) for x in buf.cpu().tolist())
         return {"mhz": 100.0 * c / max(w, 1), "cycles_per_add": c / (64.0 * iters), "probe_ms": w / 1e5}
 
+    def issue_probe(self):
+        """Shader cycles per loop iteration of one MFMA, of eight vector instructions, of both from one wave, and of the
+        two loops run by two waves of one SIMD beside each other (spd_issue_probe), on an otherwise idle chip."""
+        torch = self.torch
+        self.sync()
+        torch.cuda.synchronize()
+        buf = torch.zeros(8, dtype=torch.int64, device=self.dev)
+        for _ in range(2):
+            self.ctx.issue_probe(0, buf)
+            torch.cuda.synchronize()
+        v = [int(x) / 100.0 for x in buf.cpu().tolist()]
+        return {"mfma_alone": v[0], "valu8_alone": v[1], "mfma_then_valu8_one_wave": v[2],
+                "mfma_beside_other_waves_valu8": v[3], "valu8_beside_other_waves_mfma": v[4],
+                "unit": "shader cycles per iteration (one 32x32x16 bf16 MFMA; four v_exp_f32 + four v_fma_f32)"}
+
     def partition_switch(self):
         """Cost of a resize: spd_set_partition for a split never seen (streams are created) and for one seen
         before (streams re-used), on the caller's thread; and what the swap costs the phases: the step that adopts
@@ -453,11 +468,12 @@ def measure_config(cfg, args, steps, warmup, sweep, clock, fp8=False):
         for pp, dp in list(cfg.cu_splits) + [(100, 100)]:
             if (pp, dp) != (p_pct, d_pct):
                 splits.append(measure_split(pp, dp, max(10, steps // 2), 2))
-    clocks = switch = None
+    clocks = switch = issue = None
     if clock:
         bench.set_split(p_pct, d_pct)
         clocks = {load: bench.clock_probe(load) for load in ("idle", "prefill", "decode", "both")}
         switch = bench.partition_switch()
+        issue = bench.issue_probe()
 
     r = head["decode_per_prefill"]
     tokens_per_step = (bench.T if args.only != "decode" else 0) + (r * bench.B if args.only != "prefill" else 0)
@@ -495,6 +511,7 @@ def measure_config(cfg, args, steps, warmup, sweep, clock, fp8=False):
     if clocks:
         part["clock_probe"] = clocks
         part["partition_switch"] = switch
+        part["issue_probe"] = issue
     bench.close()
     del bench
     gc.collect()

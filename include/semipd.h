@@ -493,6 +493,15 @@ int spd_phase_read(spd_ctx* ctx, int phase, const void* src, uint64_t bytes);
  * that load (cycle ticks / constant ticks x 100 MHz).  1 <= iters <= 2^32. */
 int spd_clock_probe(spd_ctx* ctx, void* hip_stream, uint64_t iters, uint64_t* dev_out);
 
+/* Does matrix work overlap vector work inside one wave, or only between the waves of a SIMD?  One workgroup
+ * on `hip_stream` (null: the default stream) writes to device dev_out[8] (8-byte aligned), in hundredths of
+ * a shader cycle per loop iteration: [0] one 32x32x16 bf16 MFMA per iteration, [1] eight independent vector
+ * instructions (four v_exp_f32, four v_fma_f32), [2] the MFMA followed by those eight, all three from one
+ * wave alone; [3] the MFMA loop again while another wave of the same SIMD runs the vector loop beside it,
+ * [4] that other wave's vector loop.  If [2] is about [0] + [1] while [3] and [4] stay about [0] and [1], an
+ * MFMA holds the wave that issued it and the two kinds of work overlap only between waves. */
+int spd_issue_probe(spd_ctx* ctx, void* hip_stream, uint64_t* dev_out);
+
 /* Run a tiny kernel of `n_blocks` workgroups on the phase's current stream and
  * report, to host ids[cap], the distinct hardware (XCD << 16 | SE << 8 | CU) ids that ran
  * them; used to check that a masked stream stays on its CUs. */

@@ -441,6 +441,14 @@ extern "C" int spd_clock_probe(spd_ctx* ctx, void* hip_stream, uint64_t iters, u
   return SPD_OK;
 }
 
+extern "C" int spd_issue_probe(spd_ctx* ctx, void* hip_stream, uint64_t* dev_out) {
+  if (!ctx || !dev_out || ((uintptr_t)dev_out & 7)) return SPD_EINVAL;
+  if (ctx->device < 0) return SPD_ESTATE;
+  SPD_HIP(hipSetDevice(ctx->device));
+  SPD_HIP(launch_issue_probe(dev_out, (hipStream_t)hip_stream));
+  return SPD_OK;
+}
+
 extern "C" int spd_phase_probe_cus(spd_ctx* ctx, int phase, int32_t n_blocks, int32_t* ids, int32_t cap,
                                    int32_t* n_ids) {
   if (!ctx || phase < 0 || phase > 1 || n_blocks <= 0 || n_blocks > (1 << 20) || !ids || cap <= 0 || !n_ids)

@@ -374,6 +374,79 @@ hipError_t launch_clock_probe(uint64_t iters, uint64_t* d_out, hipStream_t strea
   return hipGetLastError();
 }
 
+// Does matrix work overlap vector work inside one wave, or only between waves?  One workgroup of five waves: waves 0
+// and 4 share a SIMD, the other three idle.  Wave 0 times (shader cycles per iteration, 256 iterations each)
+//   out[0]: one 32x32x16 bf16 MFMA per iteration (four accumulators in rotation),
+//   out[1]: eight independent vector instructions per iteration (four v_exp_f32, four v_fma_f32),
+//   out[2]: the MFMA followed by the same eight vector instructions,
+// then, after a barrier, out[3]: its MFMA loop again while wave 4 runs the vector loop beside it (out[4]: wave 4's
+// cycles per iteration in that phase).  out[5] keeps the results alive.
+__global__ __launch_bounds__(320) void issue_probe_kernel(uint64_t* __restrict__ out) {
+  typedef float f32x16_ __attribute__((ext_vector_type(16)));
+  typedef __bf16 bf16x8_ __attribute__((ext_vector_type(8)));
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  constexpr int N = 256;
+  f32x16_ acc[4];
+  for (int i = 0; i < 4; ++i)
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  const uint4 araw = uint4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+  const bf16x8_ a = __builtin_bit_cast(bf16x8_, araw);
+  float x[8];
+  for (int j = 0; j < 8; ++j) x[j] = 0.001f * (float)(threadIdx.x + j);
+  auto valu8 = [&]() {
+    asm volatile("v_exp_f32 %0, %0\n\tv_exp_f32 %1, %1\n\tv_exp_f32 %2, %2\n\tv_exp_f32 %3, %3\n\t"
+                 "v_fma_f32 %4, %4, %4, %4\n\tv_fma_f32 %5, %5, %5, %5\n\tv_fma_f32 %6, %6, %6, %6\n\tv_fma_f32 %7, %7, %7, %7"
+                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]));
+  };
+  auto mfma1 = [&](int i) { acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, a, acc[i & 3], 0, 0, 0); };
+  uint64_t t[6] = {0, 0, 0, 0, 0, 0};
+  if (wave == 0) {
+    uint64_t t0 = __builtin_readcyclecounter();
+#pragma unroll 4
+    for (int i = 0; i < N; ++i) { mfma1(i); __builtin_amdgcn_sched_barrier(0); }
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+    t[0] = __builtin_readcyclecounter() - t0;
+    t0 = __builtin_readcyclecounter();
+#pragma unroll 4
+    for (int i = 0; i < N; ++i) { valu8(); __builtin_amdgcn_sched_barrier(0); }
+    t[1] = __builtin_readcyclecounter() - t0;
+    t0 = __builtin_readcyclecounter();
+#pragma unroll 4
+    for (int i = 0; i < N; ++i) { mfma1(i); __builtin_amdgcn_sched_barrier(0); valu8(); __builtin_amdgcn_sched_barrier(0); }
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+    t[2] = __builtin_readcyclecounter() - t0;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const uint64_t t0 = __builtin_readcyclecounter();
+#pragma unroll 4
+    for (int i = 0; i < N; ++i) { mfma1(i); __builtin_amdgcn_sched_barrier(0); }
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+    t[3] = __builtin_readcyclecounter() - t0;
+  } else if (wave == 4) {
+    const uint64_t t0 = __builtin_readcyclecounter();
+#pragma unroll 4
+    for (int i = 0; i < N; ++i) { valu8(); __builtin_amdgcn_sched_barrier(0); }
+    t[4] = __builtin_readcyclecounter() - t0;
+  }
+  float keep = x[0] + x[1] + x[2] + x[3] + x[4] + x[5] + x[6] + x[7];
+  for (int i = 0; i < 4; ++i) keep += acc[i][0];
+  if ((threadIdx.x & 63) == 0) {
+    if (wave == 0) {
+      for (int i = 0; i < 4; ++i) out[i] = t[i] * 100 / N;        // hundredths of a cycle per iteration
+      out[5] = (uint64_t)__builtin_bit_cast(uint32_t, keep);
+    } else if (wave == 4) {
+      out[4] = t[4] * 100 / N;
+      out[6] = (uint64_t)__builtin_bit_cast(uint32_t, keep);
+    }
+  }
+}
+
+hipError_t launch_issue_probe(uint64_t* d_out, hipStream_t stream) {
+  hipLaunchKernelGGL(issue_probe_kernel, dim3(1), dim3(320), 0, stream, d_out);
+  return hipGetLastError();
+}
+
 hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, int cus, hipStream_t stream) {
   hipLaunchKernelGGL(copy_kernel, dim3((unsigned)cus * 16), dim3(256), 0, stream, (uint4*)dst, (const uint4*)src, bytes / 16);
   return hipGetLastError();

@@ -352,8 +352,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     // all unless the row sum says that the reference is out of range (an item's first tile, where
     // m = -inf makes every p infinite or NaN, or a tile whose scores exceed the reference by 2^60):
     // then the reference moves to the true maximum, the accumulators are rescaled, and p is redone.
-    // The softmax runs at raised priority: its vector instructions then slip in between the other wave's MFMAs
-    // (which hold that wave, not the vector unit), instead of queueing behind them.
+    // The softmax runs at raised priority: its vector instructions then go out between the other wave's MFMAs
+    // (each of which takes only a few issue cycles of the SIMD) instead of queueing behind them.
     __builtin_amdgcn_s_setprio(3);
     uint32_t pb[2][8];
     auto softmax_p = [&](float mc) -> float {
