@@ -315,6 +315,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
 
     // ---- S^T = K . Q^T.  Operand i: block b = i % 2 (32 keys), k-step ks = i / 2; LDS reads run
     // RING operands ahead of the MFMAs that consume them.
+    __builtin_amdgcn_s_setprio(0);
     f32x16 S[2];
 #pragma unroll
     for (int b = 0; b < 2; ++b)
@@ -352,8 +353,10 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     // all unless the row sum says that the reference is out of range (an item's first tile, where
     // m = -inf makes every p infinite or NaN, or a tile whose scores exceed the reference by 2^60):
     // then the reference moves to the true maximum, the accumulators are rescaled, and p is redone.
-    // The softmax runs at raised priority: its vector instructions then go out between the other wave's MFMAs
-    // (each of which takes only a few issue cycles of the SIMD) instead of queueing behind them.
+    // A wave's priority rises as it gets on with its tile: first product 0, softmax 3, second product 1.  The wave
+    // that is further along is served first, so the two waves of a SIMD fall out of step instead of contending
+    // phase by phase, and the softmax's vector instructions go out between the other wave's MFMAs (each of which
+    // takes only a few issue cycles of the SIMD) instead of queueing behind them.
     __builtin_amdgcn_s_setprio(3);
     uint32_t pb[2][8];
     auto softmax_p = [&](float mc) -> float {
@@ -404,7 +407,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
       psum = softmax_p(m * c);
     }
     l += psum;
-    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_s_setprio(1);
 
     // ---- O^T += V^T . P^T : 16-key step kk multiplies with S^T block kk/2, registers 8*(kk%2) .. +7;
     // the operands of step kk + 1 are read while step kk multiplies
