@@ -176,9 +176,13 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
 
   // ---- LDS operand addresses (byte offsets inside a stage)
   // K operand (S^T block b, k-step ks): row 32 b + n32, chunk 2 ks + hh
-  int k_off[KS];
+  // (192 dims: the swizzle touches the low three bits of the chunk number only, so k-steps four apart differ by
+  // 128 bytes and share a lane address; that frees eight registers)
+  constexpr int KOFFS = DQK == 192 ? 4 : KS;
+  int k_off[KOFFS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) k_off[ks] = n32 * (CHK * 16) + (((2 * ks + hh) ^ k_swz<DQK>(n32)) * 16);
+  for (int ks = 0; ks < KOFFS; ++ks) k_off[ks] = n32 * (CHK * 16) + (((2 * ks + hh) ^ k_swz<DQK>(n32)) * 16);
+  auto k_addr = [&](int ks) -> int { return k_off[ks % KOFFS] + (ks / KOFFS) * 128; };
   // V operand (16-key step kk, value block blk): two transpose reads.  In each group of 16 lanes
   // lane r supplies row (key) 4 hh + r / 4 and dims 4 (r % 4) .. + 3 of the group's 16 dims; the
   // hardware hands lane i of the group dim i of those 4 keys.
@@ -198,7 +202,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
   int k_off2[KS], v_off2[VB];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
-    k_off2[ks] = k_off[ks] + 2 * STAGE_BYTES;
+    k_off2[ks] = k_addr(ks) + 2 * STAGE_BYTES;
     asm volatile("" : "+v"(k_off2[ks]));        // a value of its own, not "k_off + constant" to be recomputed
   }
 #pragma unroll
@@ -305,7 +309,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
 
     const char* sbase = UNROLL ? smem + (ST & 1) * STAGE_BYTES : smem + ST * STAGE_BYTES;
     auto read_k = [&](int i) -> uint4 {
-      return *(const uint4*)(sbase + (UNROLL && ST >= 2 ? k_off2[i / 2] : k_off[i / 2]) + (i % 2) * (32 * CHK * 16));
+      return *(const uint4*)(sbase + (UNROLL && ST >= 2 ? k_off2[i / 2] : k_addr(i / 2)) + (i % 2) * (32 * CHK * 16));
     };
     auto read_v = [&](int i, int half) -> s16x4 {
       const int kk = i / VB, blk = i % VB;
@@ -331,12 +335,15 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
       if (i + RING < NS) ring[i % RING] = read_k(i + RING);
       __builtin_amdgcn_sched_barrier(0);
     }
-    // first V operands: in flight while the vector units do the softmax
-    s16x4 vr[2][VB][2];                         // [parity of kk][value block][half]
+    // first V operands: in flight while the vector units do the softmax.  Operand j = 16-key step j / VB, value
+    // block j % VB; a queue of VQ operands, read VAH ahead of the MFMA that takes them (a whole step ahead, two
+    // steps' worth of registers; with 192 dims two operands ahead in a queue of three: registers are short there)
+    constexpr int VAH = DQK > 128 ? 2 : VB, VQ = DQK > 128 ? VAH + 1 : 2 * VB;
+    s16x4 vq[VQ][2];
 #pragma unroll
-    for (int blk = 0; blk < VB; ++blk) {
-      vr[0][blk][0] = read_v(blk, 0);
-      vr[0][blk][1] = read_v(blk, 1);
+    for (int j = 0; j < VAH; ++j) {
+      vq[j][0] = read_v(j, 0);
+      vq[j][1] = read_v(j, 1);
     }
 
     // lane holds, for the query at position pos, keys kv0 + 32b + 8*(i/4) + 4*hh + i%4
@@ -375,11 +382,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
         }
       return (ls[0] + ls[1]) + (ls[2] + ls[3]);
     };
-    // (the 192-dim variant has no registers to keep S alive for a second pass: it takes the maximum first, every tile)
-    constexpr bool LAZY = DQK <= 128;
-    float psum = 0.f;
-    if constexpr (LAZY) psum = softmax_p(m * c);
-    if (!LAZY || __builtin_amdgcn_ballot_w64(!(psum < 0x1p60f)) != 0) {
+    float psum = softmax_p(m * c);
+    if (__builtin_amdgcn_ballot_w64(!(psum < 0x1p60f)) != 0) {
       float mx = S[0][0];
 #pragma unroll
       for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[0][i]);
@@ -394,23 +398,20 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
         mx = fmaxf(mx, mx2);
       }
       const float m_new = fmaxf(m, mx);
-      // (the eager variant: the running maximum rarely moves after the first tiles, rescale only when some lane needs it)
-      if (LAZY || __builtin_amdgcn_ballot_w64(m_new > m) != 0) {
-        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
-        l *= alpha;
+      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+      l *= alpha;
 #pragma unroll
-        for (int blk = 0; blk < VB; ++blk)
+      for (int blk = 0; blk < VB; ++blk)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) O[blk][e] *= alpha;
-        m = m_new;
-      }
+        for (int e = 0; e < 16; ++e) O[blk][e] *= alpha;
+      m = m_new;
       psum = softmax_p(m * c);
     }
     l += psum;
     __builtin_amdgcn_s_setprio(1);
 
     // ---- O^T += V^T . P^T : 16-key step kk multiplies with S^T block kk/2, registers 8*(kk%2) .. +7;
-    // the operands of step kk + 1 are read while step kk multiplies
+    // operand j + VAH is read while operand j multiplies
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kk = 0; kk < BN / 16; ++kk) {
@@ -418,13 +419,14 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
                                pb[kk >> 1][4 * (kk & 1) + 3]};
 #pragma unroll
       for (int blk = 0; blk < VB; ++blk) {
-        const uint2 lo = __builtin_bit_cast(uint2, vr[kk & 1][blk][0]), hi = __builtin_bit_cast(uint2, vr[kk & 1][blk][1]);
+        const int j = kk * VB + blk;
+        const uint2 lo = __builtin_bit_cast(uint2, vq[j % VQ][0]), hi = __builtin_bit_cast(uint2, vq[j % VQ][1]);
         const uint4 a = uint4{lo.x, lo.y, hi.x, hi.y};
         O[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, praw),
                                                          O[blk], 0, 0, 0);
-        if (kk + 1 < BN / 16) {
-          vr[(kk + 1) & 1][blk][0] = read_v((kk + 1) * VB + blk, 0);
-          vr[(kk + 1) & 1][blk][1] = read_v((kk + 1) * VB + blk, 1);
+        if (j + VAH < (BN / 16) * VB) {
+          vq[(j + VAH) % VQ][0] = read_v(j + VAH, 0);
+          vq[(j + VAH) % VQ][1] = read_v(j + VAH, 1);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
