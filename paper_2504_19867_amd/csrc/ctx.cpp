@@ -136,6 +136,7 @@ extern "C" int spd_ctx_destroy(spd_ctx* ctx) {
         if (st.done) (void)hipEventDestroy(st.done);
       }
       if (s.workspace) (void)hipFree(s.workspace);
+      for (auto& r : s.ws_retired) (void)hipFree(r.first);
       for (hipEvent_t e : {s.ev_start, s.ev_end, s.ev_switch, s.ev_cross})
         if (e) (void)hipEventDestroy(e);
       for (auto& pair : s.kev)
@@ -308,6 +309,17 @@ bool phase_step_done(spd_ctx* ctx, int phase, uint64_t seq) {
   return false;
 }
 
+static void workspace_release_retired(spd_ctx* ctx, int phase) {
+  spd_phase_state& s = ctx->phase[phase];
+  std::lock_guard<std::mutex> lk(s.ws_mu);
+  size_t keep = 0;
+  for (auto& r : s.ws_retired) {
+    if (phase_step_done(ctx, phase, r.second)) (void)hipFree(r.first);
+    else s.ws_retired[keep++] = r;
+  }
+  s.ws_retired.resize(keep);
+}
+
 int workspace_reserve(spd_ctx* ctx, int phase, size_t bytes, char** out) {
   spd_phase_state& s = ctx->phase[phase];
   if (s.ws_cap < bytes) {
@@ -315,14 +327,15 @@ int workspace_reserve(spd_ctx* ctx, int phase, size_t bytes, char** out) {
     while (cap < bytes) cap *= 2;
     char* d = nullptr;
     SPD_HIP(hipMalloc((void**)&d, cap));
+    // Earlier steps of this phase may still read the old buffer: it is kept until the last of them (the step
+    // issued most recently; the one being built takes the new buffer) is known to have finished.  No wait here.
     if (s.workspace) {
-      // earlier steps of this phase may still read the old buffer
-      for (auto& kv : ctx->stream_cache)
-        if (kv.first.back() == (uint32_t)phase) (void)hipStreamSynchronize(kv.second);
-      (void)hipFree(s.workspace);
+      std::lock_guard<std::mutex> lk(s.ws_mu);
+      s.ws_retired.emplace_back(s.workspace, s.issue_seq.load(std::memory_order_acquire));
     }
     s.workspace = d;
     s.ws_cap = cap;
+    workspace_release_retired(ctx, phase);
   }
   *out = s.workspace;
   return SPD_OK;
@@ -371,6 +384,7 @@ extern "C" int spd_phase_sync(spd_ctx* ctx, int phase) {
   const uint64_t issued = ctx->phase[phase].issue_seq.load(std::memory_order_acquire);
   SPD_HIP(hipStreamSynchronize(s));
   raise_done_seq(ctx->phase[phase], issued);
+  workspace_release_retired(ctx, phase);
   return SPD_OK;
 }
 

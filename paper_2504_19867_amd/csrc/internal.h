@@ -140,6 +140,10 @@ struct spd_phase_state {
   bool timed = false;
   char* workspace = nullptr;           // split-K partials (decode)
   size_t ws_cap = 0;
+  // workspaces outgrown, with the number of the last step that may still read them: freed once that step has
+  // finished (looked at when the workspace grows again, in spd_phase_sync and when the context goes)
+  std::vector<std::pair<char*, uint64_t>> ws_retired;
+  std::mutex ws_mu;                    // the list above (a step's thread against another thread's spd_phase_sync)
   // last split-K chunk choice of the MLA decode (re-derived when the batch has changed by more than a little)
   int ck_B = 0, ck_cus = 0, ck_chunk = 0;
   int64_t ck_sum = 0;

@@ -117,3 +117,33 @@ def test_chunked_prefill_long_prefix_and_argument_checks():
         gp.pool.prefill_step([5], [0, 4096], big, dev_bf16(k[:4096]), dev_bf16(v[:4096]), ob, 8, 2, 128, 128, scale, prefix_lens=[n])
     assert gp.pool.kv_free_list() == free_before
     gp.close()
+
+
+def test_workspace_grows_between_steps_in_flight():
+    """Two chunked steps issued back to back without a wait between them, the second with a context that
+    no longer fits the gather workspace of the first (16 MiB to start with): the first step still reads the
+    old workspace when the second takes a new one, and both come out right."""
+    layer = W.LayerShape("gqa", 8, 2, 64, 64, 16)              # 512 bytes of K and V per cached row
+    small, big = 600, 33000                                     # 0.3 MiB, then 16.9 MiB of gathered context
+    gp = GpuPool(layer, (small + big) // 16 + 8, poison=True)
+    scale = 1.0 / math.sqrt(64)
+    qs, ks, vs, _ = W.prefill_inputs(layer, (small,), seed=311)
+    qb, kb, vb, _ = W.prefill_inputs(layer, (big,), seed=312)
+    cut_s, cut_b = small - 40, big - 24
+    # the prefixes, each in one un-chunked step (no workspace), then drained
+    for rid, (q, k, v, cut) in ((1, (qs, ks, vs, cut_s)), (2, (qb, kb, vb, cut_b))):
+        o = torch.empty((cut, 8, 64), dtype=torch.bfloat16, device=DEV)
+        gp.pool.prefill_step([rid], [0, cut], dev_bf16(q[:cut]), dev_bf16(k[:cut]), dev_bf16(v[:cut]), o, 8, 2, 64, 64, scale)
+    gp.ctx.phase_sync(PRE)
+    out_s = torch.empty((small - cut_s, 8, 64), dtype=torch.bfloat16, device=DEV)
+    out_b = torch.empty((big - cut_b, 8, 64), dtype=torch.bfloat16, device=DEV)
+    args_s = [dev_bf16(x[cut_s:]) for x in (qs, ks, vs)]
+    args_b = [dev_bf16(x[cut_b:]) for x in (qb, kb, vb)]
+    gp.pool.prefill_step([1], [0, small - cut_s], *args_s, out_s, 8, 2, 64, 64, scale, prefix_lens=[cut_s])
+    gp.pool.prefill_step([2], [0, big - cut_b], *args_b, out_b, 8, 2, 64, 64, scale, prefix_lens=[cut_b])
+    gp.ctx.phase_sync(PRE)
+    want_s = OA.chunk_attention(f64(qs[cut_s:]), f64(ks), f64(vs), scale)
+    want_b = OA.chunk_attention(f64(qb[cut_b:]), f64(kb), f64(vb), scale)
+    assert_parity(host_f64(out_s), want_s, "step that read the workspace before it grew")
+    assert_parity(host_f64(out_b), want_b, "step that made it grow")
+    gp.close()
