@@ -183,19 +183,23 @@ class Bench:
         return self.ctx.get_partition()[:2]
 
     def read_ceiling(self, phase, nbytes=4 << 30, reps=6):
-        """GB/s of a read-only streaming kernel (eight 16-byte loads in flight per lane, nothing written) over
-        `nbytes` on the phase's stream, the other phase idle: what the phase's CU share can read out of HBM at
-        best, the yardstick of the decode kernels."""
+        """GB/s of the read-only streaming kernels over `nbytes` on the phase's stream, the other phase idle:
+        what the phase's CU share can read out of HBM at best, the yardstick of the decode kernels.  Two ways of
+        reading (eight 16-byte register loads in flight per lane; 1 KiB loads into LDS, 16 in flight per wave):
+        returns (the faster of the two, {"register_loads": GB/s, "lds_loads": GB/s})."""
         torch = self.torch
         if not hasattr(self, "_rd"):
             self._rd = torch.empty(nbytes // 8, dtype=torch.int64, device=self.dev).random_()
-        self.ctx.phase_read(phase, self._rd, nbytes)
-        self.ctx.phase_sync(phase)
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            self.ctx.phase_read(phase, self._rd, nbytes)
-        self.ctx.phase_sync(phase)
-        return nbytes * reps / (time.perf_counter() - t0) / 1e9
+        got = {}
+        for name, fn in (("register_loads", self.ctx.phase_read), ("lds_loads", self.ctx.phase_read_lds)):
+            fn(phase, self._rd, nbytes)
+            self.ctx.phase_sync(phase)
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn(phase, self._rd, nbytes)
+            self.ctx.phase_sync(phase)
+            got[name] = nbytes * reps / (time.perf_counter() - t0) / 1e9
+        return max(got.values()), got
 
     def clock_probe(self, load, ms=4.0):
         """The shader clock the chip holds under `load` ("idle", "prefill", "decode", "both"): one wave on a
@@ -423,7 +427,7 @@ def measure_config(cfg, args, steps, warmup, sweep, clock, fp8=False):
 
     def measure_split(pp, dp, steps, warmup, only=None):
         p_cus, d_cus = bench.set_split(pp, dp)
-        read_gbs = bench.read_ceiling(DEC)
+        read_gbs, read_by = bench.read_ceiling(DEC)
         if args.decode_per_prefill > 0 or only:
             # fixed mix in lockstep (profiling aid), or one phase alone
             r = max(1, args.decode_per_prefill)
@@ -443,7 +447,7 @@ def measure_config(cfg, args, steps, warmup, sweep, clock, fp8=False):
         dec_gbs = bench.decode_bytes / (median(dk) * 1e-3) / 1e9 if dk else None
         solo_dec_gbs = bench.decode_bytes / (solo_d_k * 1e-3) / 1e9
         return {"split": f"{pp}/{dp}", "prefill_cus": p_cus, "decode_cus": d_cus, "decode_per_prefill": r,
-                "ms_per_step": wall_ms, "decode_share_read_gbs": read_gbs,
+                "ms_per_step": wall_ms, "decode_share_read_gbs": read_gbs, "decode_share_read_gbs_by_method": read_by,
                 "prefill_tok_s": bench.T / wall_ms * 1e3 if only != "decode" else 0.0,
                 "decode_tok_s": r * bench.B / wall_ms * 1e3 if only != "prefill" else 0.0,
                 "prefill_kernel_ms": median(pk), "decode_kernel_ms": median(dk),
@@ -504,6 +508,7 @@ def measure_config(cfg, args, steps, warmup, sweep, clock, fp8=False):
                             "kernel_ms": head["decode_kernel_ms"],
                             "bytes_per_launch": bench.decode_bytes, "share_cus": head["decode_cus"],
                             "share_read_ceiling_gbs": head["decode_share_read_gbs"],
+                            "share_read_ceiling_gbs_by_method": head["decode_share_read_gbs_by_method"],
                             "frac_of_share_read_ceiling": head["decode_frac_of_share_read"],
                             "solo_frac_of_share_read_ceiling": head["solo"]["decode_frac_of_share_read"]},
         "splits": splits,

@@ -486,6 +486,12 @@ int spd_phase_copy(spd_ctx* ctx, int phase, void* dst, const void* src, uint64_t
  * almost nothing). */
 int spd_phase_read(spd_ctx* ctx, int phase, const void* src, uint64_t bytes);
 
+/* The same, read the way the attention kernels fetch their tiles: two workgroups per compute
+ * unit, every wave streaming a contiguous part of the buffer with load instructions that write
+ * straight into LDS, 16 KiB in flight per wave.  On a share of the chip this reads faster than
+ * the register loads above; the yardstick is the faster of the two. */
+int spd_phase_read_lds(spd_ctx* ctx, int phase, const void* src, uint64_t bytes);
+
 /* One wave, on the caller's stream `hip_stream` (a hipStream_t; null: the default stream), runs
  * 64 * iters dependent integer adds and writes to device dev_out[3] (8-byte aligned): the time
  * that took in ticks of the constant 100 MHz counter, in ticks of the shader cycle counter,

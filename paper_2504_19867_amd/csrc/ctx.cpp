@@ -446,6 +446,16 @@ extern "C" int spd_phase_read(spd_ctx* ctx, int phase, const void* src, uint64_t
   return SPD_OK;
 }
 
+extern "C" int spd_phase_read_lds(spd_ctx* ctx, int phase, const void* src, uint64_t bytes) {
+  if (!ctx || phase < 0 || phase > 1 || !src || bytes == 0 || bytes % 16 != 0) return SPD_EINVAL;
+  if ((uintptr_t)src & 15) return SPD_EINVAL;
+  hipStream_t stream;
+  int rc = phase_enter(ctx, phase, &stream);
+  if (rc != SPD_OK) return rc;
+  SPD_HIP(launch_read_lds(src, bytes, ctx->phase[phase].active_cus, nullptr, stream));
+  return SPD_OK;
+}
+
 extern "C" int spd_clock_probe(spd_ctx* ctx, void* hip_stream, uint64_t iters, uint64_t* dev_out) {
   if (!ctx || !dev_out || iters == 0 || iters > (1ull << 32)) return SPD_EINVAL;
   if ((uintptr_t)dev_out & 7) return SPD_EINVAL;

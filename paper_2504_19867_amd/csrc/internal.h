@@ -230,6 +230,7 @@ hipError_t launch_rope_append(const PoolGeom& g, char* pool_base, const TileDesc
 hipError_t launch_probe(int32_t* d_ids, int n_blocks, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, int cus, hipStream_t stream);
 hipError_t launch_read(const void* src, uint64_t bytes, int cus, uint32_t* sink, hipStream_t stream);
+hipError_t launch_read_lds(const void* src, uint64_t bytes, int cus, uint32_t* sink, hipStream_t stream);
 hipError_t launch_clock_probe(uint64_t iters, uint64_t* d_out, hipStream_t stream);
 hipError_t launch_issue_probe(uint64_t* d_out, hipStream_t stream);
 bool prefill_shape_supported(int dqk, int dv);

@@ -343,6 +343,35 @@ __global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src
   if (acc == 0x9e3779b9u && sink) sink[0] = acc;
 }
 
+// The same stream taken through LDS: every wave reads a contiguous part of the buffer with 1 KiB load instructions
+// that write straight into its 16 KiB of LDS (as the attention kernels' tile loads do), up to 16 of them in flight;
+// what is left over at the end goes the way of read_kernel.  Two workgroups per compute unit.
+__global__ __launch_bounds__(256, 2) void read_lds_kernel(const uint4* __restrict__ src, uint64_t n16, uint32_t* __restrict__ sink) {
+  __shared__ __attribute__((aligned(1024))) char lds[4 * 16384];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint64_t waves = (uint64_t)gridDim.x * 4, gw = (uint64_t)blockIdx.x * 4 + wave;
+  const uint64_t inst = n16 / 64 / waves;                   // 1 KiB instructions per wave
+  const uint4* p = src + gw * inst * 64 + lane;
+  const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds + (uint32_t)wave * 16384;
+  for (uint64_t i = 0; i < inst; ++i) {
+    const uint32_t dst = base + (uint32_t)(i & 15) * 1024;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off nt\n\ts_waitcnt vmcnt(15)" ::"s"(dst), "v"(p + i * 64) : "memory");
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  uint32_t acc = *(const uint32_t*)(lds + wave * 16384 + lane * 4);
+  for (uint64_t i = waves * inst * 64 + (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (uint64_t)gridDim.x * blockDim.x) {
+    const uint4 r = load_once(src + i);
+    acc ^= r.x ^ r.y ^ r.z ^ r.w;
+  }
+  if (acc == 0x9e3779b9u && sink) sink[0] = acc;
+}
+
+hipError_t launch_read_lds(const void* src, uint64_t bytes, int cus, uint32_t* sink, hipStream_t stream) {
+  hipLaunchKernelGGL(read_lds_kernel, dim3((unsigned)cus * 2), dim3(256), 0, stream, (const uint4*)src, bytes / 16, sink);
+  return hipGetLastError();
+}
+
 hipError_t launch_read(const void* src, uint64_t bytes, int cus, uint32_t* sink, hipStream_t stream) {
   hipLaunchKernelGGL(read_kernel, dim3((unsigned)cus * 8), dim3(256), 0, stream, (const uint4*)src, bytes / 16, sink);
   return hipGetLastError();

@@ -31,7 +31,7 @@ EXPORTS = [
     "spd_decode_worker_start", "spd_decode_worker_stop", "spd_decode_worker_steps",
     "spd_ctrl_create", "spd_ctrl_destroy", "spd_ctrl_observe_ttft", "spd_ctrl_observe_tpot", "spd_ctrl_step", "spd_ctrl_model",
     "spd_rope_inv_freq", "spd_rope_qk", "spd_ffn_gate_up", "spd_ffn_pack_gate_up",
-    "spd_decode_step_noalloc", "spd_noalloc_limits", "spd_phase_read", "spd_clock_probe", "spd_issue_probe",
+    "spd_decode_step_noalloc", "spd_noalloc_limits", "spd_phase_read", "spd_phase_read_lds", "spd_clock_probe", "spd_issue_probe",
     "spd_shm_pool_create", "spd_shm_pool_open", "spd_shm_pool_close", "spd_shm_pool_unlink", "spd_shm_pool_stats",
     "spd_shm_kv_reserve", "spd_shm_kv_free", "spd_shm_kv_block_table", "spd_shm_kv_free_list",
 ]
@@ -118,6 +118,7 @@ def _load() -> C.CDLL:
         "spd_last_hip_error": [],
         "spd_phase_copy": [vp, C.c_int, vp, vp, u64],
         "spd_phase_read": [vp, C.c_int, vp, u64],
+        "spd_phase_read_lds": [vp, C.c_int, vp, u64],
         "spd_clock_probe": [vp, vp, u64, vp],
         "spd_issue_probe": [vp, vp, vp],
         "spd_set_kernel_timing": [vp, C.c_int],
@@ -255,6 +256,9 @@ class Context:
 
     def phase_read(self, phase: int, src, nbytes: int) -> None:
         _check(lib.spd_phase_read(self.h, phase, _ptr(src), nbytes), "spd_phase_read")
+
+    def phase_read_lds(self, phase: int, src, nbytes: int) -> None:
+        _check(lib.spd_phase_read_lds(self.h, phase, _ptr(src), nbytes), "spd_phase_read_lds")
 
     def clock_probe(self, hip_stream: int, iters: int, dev_out) -> None:
         _check(lib.spd_clock_probe(self.h, hip_stream or None, iters, _ptr(dev_out)), "spd_clock_probe")

@@ -18,6 +18,7 @@ namespace spd {
 hipError_t launch_probe(int32_t*, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_copy(void*, const void*, uint64_t, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_read(const void*, uint64_t, int, uint32_t*, hipStream_t) { return hipErrorUnknown; }
+hipError_t launch_read_lds(const void*, uint64_t, int, uint32_t*, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_clock_probe(uint64_t, uint64_t*, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_issue_probe(uint64_t*, hipStream_t) { return hipErrorUnknown; }
 int scratch_resolve(int, char**) { return SPD_ESTATE; }
