@@ -232,26 +232,32 @@ __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(
   }
 }
 
-// grid (H, B), block D: merge the chunks of one (request, head).
+// grid (ceil(H / (512 / D)), B), block 128: merge the chunks of (request, head) pairs; D / 4 threads per head, four
+// output dims each.
 template <int D>
-__global__ __launch_bounds__(D) void decode_combine_kernel(bf16_t* __restrict__ out, const int32_t* __restrict__ ctx_lens,
-                                                          int H, int chunk_tiles, int max_chunks,
-                                                          const float* __restrict__ ws_o,
-                                                          const float* __restrict__ ws_ml) {
-  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+__global__ __launch_bounds__(128) void decode_combine_kernel(bf16_t* __restrict__ out, const int32_t* __restrict__ ctx_lens,
+                                                            int H, int chunk_tiles, int max_chunks,
+                                                            const float* __restrict__ ws_o,
+                                                            const float* __restrict__ ws_ml) {
+  constexpr int TPH = D / 4;                       // threads per head
+  const int h = blockIdx.x * (128 / TPH) + threadIdx.x / TPH, b = blockIdx.y, d = 4 * (threadIdx.x % TPH);
   const int n_tiles = (ctx_lens[b] + TILE_T - 1) / TILE_T;
   const int n_chunks = (n_tiles + chunk_tiles - 1) / chunk_tiles;
-  if (n_chunks <= 1) return;                      // written directly by the attention kernel
+  if (n_chunks <= 1 || h >= H) return;            // one chunk: written directly by the attention kernel
   const size_t slot0 = ((size_t)b * H + h) * max_chunks;
   float m_tot = -INFINITY;
   for (int ck = 0; ck < n_chunks; ++ck) m_tot = fmaxf(m_tot, ws_ml[(slot0 + ck) * 2]);
-  float l_tot = 0.f, o = 0.f;
+  float l_tot = 0.f;
+  f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int ck = 0; ck < n_chunks; ++ck) {
     const float wgt = __builtin_amdgcn_exp2f(ws_ml[(slot0 + ck) * 2] - m_tot);
     l_tot += ws_ml[(slot0 + ck) * 2 + 1] * wgt;
-    o += ws_o[(slot0 + ck) * D + d] * wgt;
+    o += *(const f32x4*)(ws_o + (slot0 + ck) * D + d) * wgt;
   }
-  out[((size_t)b * H + h) * D + d] = to_bf16_rne(o / l_tot);
+  uint2 pk;
+  pk.x = pack_bf16_rne(o[0] / l_tot, o[1] / l_tot);
+  pk.y = pack_bf16_rne(o[2] / l_tot, o[3] / l_tot);
+  *(uint2*)(out + ((size_t)b * H + h) * D + d) = pk;
 }
 
 template <int D>
@@ -265,7 +271,7 @@ static hipError_t launch_decode_gqa_t(const PoolGeom& g, const char* pool_base, 
                      d_bt, bt_stride, d_items, g.Hkv, H, H / g.Hkv, c, chunk_tiles, max_chunks, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || max_chunks <= 1) return e;
-  hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(H, B), dim3(D), 0, stream, (bf16_t*)out, d_ctx_lens, H, chunk_tiles,
+  hipLaunchKernelGGL(decode_combine_kernel<D>, dim3((unsigned)(H + 512 / D - 1) / (512 / D), B), dim3(128), 0, stream, (bf16_t*)out, d_ctx_lens, H, chunk_tiles,
                      max_chunks, ws_o, ws_ml);
   return hipGetLastError();
 }

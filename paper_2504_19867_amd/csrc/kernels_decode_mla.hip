@@ -376,26 +376,32 @@ __global__ __launch_bounds__(256, 2) void decode_mla_kernel(
   }
 }
 
-// grid (H, B), block 512: merge the chunks of one (request, head); one thread per output dim.
-__global__ __launch_bounds__(512) void decode_mla_combine_kernel(bf16_t* __restrict__ out,
+// grid (H, B), block 128: merge the chunks of one (request, head); four output dims per thread, so that all
+// workgroups of a batch are resident at once and the launch is one round of loads deep.
+__global__ __launch_bounds__(128) void decode_mla_combine_kernel(bf16_t* __restrict__ out,
                                                                 const int32_t* __restrict__ ctx_lens, int H,
                                                                 int chunk_steps, int max_chunks,
                                                                 const float* __restrict__ ws_o,
                                                                 const float* __restrict__ ws_ml) {
-  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  static_assert(mla::DV == 4 * 128, "one thread per four output dims");
+  const int h = blockIdx.x, b = blockIdx.y, d = 4 * threadIdx.x;
   const int n_steps = (ctx_lens[b] + mla::STEP_T - 1) / mla::STEP_T;
   const int n_chunks = (n_steps + chunk_steps - 1) / chunk_steps;
   if (n_chunks <= 1) return;
   const size_t slot0 = ((size_t)b * H + h) * max_chunks;
   float m_tot = -INFINITY;
   for (int ck = 0; ck < n_chunks; ++ck) m_tot = fmaxf(m_tot, ws_ml[(slot0 + ck) * 2]);
-  float l_tot = 0.f, o = 0.f;
+  float l_tot = 0.f;
+  f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int ck = 0; ck < n_chunks; ++ck) {
     const float wgt = __builtin_amdgcn_exp2f(ws_ml[(slot0 + ck) * 2] - m_tot);
     l_tot += ws_ml[(slot0 + ck) * 2 + 1] * wgt;
-    o += ws_o[(slot0 + ck) * mla::DV + d] * wgt;
+    o += *(const f32x4*)(ws_o + (slot0 + ck) * mla::DV + d) * wgt;
   }
-  out[((size_t)b * H + h) * mla::DV + d] = (bf16_t)(mla_pack_bf16(o / l_tot, 0.f) & 0xffffu);
+  uint2 pk;
+  pk.x = mla_pack_bf16(o[0] / l_tot, o[1] / l_tot);
+  pk.y = mla_pack_bf16(o[2] / l_tot, o[3] / l_tot);
+  *(uint2*)(out + ((size_t)b * H + h) * mla::DV + d) = pk;
 }
 
 int decode_mla_step_tokens() { return mla::STEP_T; }
@@ -417,7 +423,7 @@ hipError_t launch_decode_mla(const PoolGeom& g, const char* pool_base, const voi
                        (const int2*)d_items, H, c, chunk_steps, max_chunks, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || max_chunks <= 1) return e;
-  hipLaunchKernelGGL(decode_mla_combine_kernel, dim3(H, B), dim3(512), 0, stream, (bf16_t*)out, d_ctx_lens, H,
+  hipLaunchKernelGGL(decode_mla_combine_kernel, dim3(H, B), dim3(128), 0, stream, (bf16_t*)out, d_ctx_lens, H,
                      chunk_steps, max_chunks, ws_o, ws_ml);
   return hipGetLastError();
 }

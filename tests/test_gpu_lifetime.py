@@ -100,3 +100,25 @@ def test_a_failing_step_leaves_the_staged_partition_staged():
     gp.ctx.phase_sync(PRE)
     gp.ctx.phase_sync(DEC)
     gp.close()
+
+
+def test_read_only_yardsticks_take_any_multiple_of_16_bytes():
+    """The two streaming-read kernels of the measurement aids: sizes below one load instruction per wave, ragged
+    tails and a few MiB all run to completion on either phase; sizes and pointers off the 16-byte grid are refused."""
+    ctx = S.Context(0)
+    total, _, _ = ctx.device_info()
+    ctx.set_partition(total // 2, total // 2)
+    buf = torch.zeros((8 << 20) + 64, dtype=torch.uint8, device=DEV)
+    for read in (ctx.phase_read, ctx.phase_read_lds):
+        for phase in (PRE, DEC):
+            for nbytes in (16, 1024, 1040, (1 << 20) + 48, 8 << 20):
+                read(phase, buf, nbytes)
+            ctx.phase_sync(phase)
+        for bad in (0, 8, 1000):
+            with pytest.raises(S.SpdError) as e:
+                read(DEC, buf, bad)
+            assert e.value.status == S.SPD_EINVAL
+        with pytest.raises(S.SpdError) as e:
+            read(DEC, buf[8:], 1024)
+        assert e.value.status == S.SPD_EINVAL
+    ctx.close()
