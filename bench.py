@@ -515,6 +515,14 @@ def measure_config(cfg, args, steps, warmup, sweep, clock, fp8=False):
     }
     if clocks:
         part["clock_probe"] = clocks
+        # the same fractions against the share's peak at the shader clock the probe measured under that load
+        # (the published peak is at 2.4 GHz; under load the chip runs below it)
+        rf = part["roofline"]
+        nominal = clocks["idle"]["mhz"]
+        rf["frac_of_share_peak_at_measured_clock"] = rf["frac_of_share_peak"] * nominal / clocks["both"]["mhz"]
+        if head["solo"].get("prefill_tflops"):
+            rf["solo_frac_of_share_peak"] = head["solo"]["prefill_tflops"] / (PEAK_BF16_TFLOPS * head["prefill_cus"] / bench.total_cus)
+            rf["solo_frac_of_share_peak_at_measured_clock"] = rf["solo_frac_of_share_peak"] * nominal / clocks["prefill"]["mhz"]
         part["partition_switch"] = switch
         part["issue_probe"] = issue
     bench.close()
