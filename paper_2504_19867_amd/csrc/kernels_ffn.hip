@@ -21,7 +21,8 @@
 // spreads 16 consecutive rows over all banks.
 //
 // Decode batches (up to 256 tokens) are bound by reading the weights once: the same kernel with smaller
-// tiles (128 x 128 with four waves, 64 x 128 with a ring of six stages; two workgroups per compute unit),
+// tiles (128 x 128 with four waves, 64 x 128 with a ring of six stages, two workgroups per compute unit; 64 x 256
+// with eight waves and a ring of seven stages where that still gives every unit a workgroup),
 // so that every compute unit of the share has a workgroup and more weight bytes are in flight per unit.
 #include "internal.h"
 
@@ -53,15 +54,21 @@ __device__ inline void dma16s(const void* sbase, uint32_t voff, uint32_t lds_byt
 // <4, 4, 4>: 256 x 256 for prompt batches.  For small batches the product is bound by reading the
 // weights once, and what counts is how many weight bytes a CU keeps in flight: <2, 2, 4>: 128 x 128,
 // four waves, two workgroups per CU, for up to 128 tokens; <1, 2, 6>: 64 x 128 with a ring of six
-// 12 KiB stages, of which 8 KiB are weights, two workgroups per CU, for up to 64 tokens.
+// 12 KiB stages, of which 8 KiB are weights, two workgroups per CU, for up to 64 tokens; <1, 4, 7>: 64 x 256,
+// eight waves, a ring of seven 20 KiB stages of which 16 KiB are weights (x is a fifth of what a workgroup
+// loads instead of a third), one workgroup per CU.
 template <int MB, int WNW, int NSTAGE>
 __global__ __launch_bounds__(128 * WNW, 2) void ffn_gate_up_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
                                                                    bf16_t* __restrict__ out, int T, int K, int I, int tiles_m,
                                                                    int tiles_n, int xcds) {
   constexpr int WAVES = 2 * WNW, BM = 64 * MB, BNP = 64 * WNW, PD = NSTAGE - 1;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BNP * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
-  constexpr int LPW = (A_BYTES + B_BYTES) / 1024 / WAVES;   // 1 KiB load instructions per wave per slice
-  static_assert((A_BYTES + B_BYTES) / 1024 == LPW * WAVES && (A_BYTES / 1024) % WAVES == 0, "loads divide evenly over the waves");
+  // 1 KiB load instructions per wave per slice.  Where x has fewer pieces than there are waves (a 64-token tile under
+  // eight waves), every wave loads one: piece wave % A_LOADS, so two waves write the same bytes to the same place.
+  constexpr int A_LOADS = A_BYTES / 1024, B_LOADS = B_BYTES / 1024;
+  constexpr bool A_SHARED = A_LOADS < WAVES;
+  constexpr int LPW = A_SHARED ? 1 + B_LOADS / WAVES : (A_LOADS + B_LOADS) / WAVES;
+  static_assert(B_LOADS % WAVES == 0 && (A_SHARED ? WAVES % A_LOADS == 0 : A_LOADS % WAVES == 0), "loads divide evenly over the waves");
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -102,11 +109,15 @@ __global__ __launch_bounds__(128 * WNW, 2) void ffn_gate_up_kernel(const bf16_t*
   // ---- slice loads.  Load instruction ii = wave + WAVES j fills the 64 consecutive 16-byte slots
   // [64 ii, 64 ii + 64) of the stage: x rows first (row = slot / 4), then weight rows; slot s of a
   // row holds the row's chunk s ^ ((row >> 2) & 3).  Token rows past T re-read row T - 1.
-  constexpr int A_LOADS = A_BYTES / 1024;
+  // piece number of this wave's load j: below A_LOADS a piece of x, from there on pieces of the weights
+  auto piece_of = [&](int j) __attribute__((always_inline)) -> int {
+    if constexpr (A_SHARED) return j == 0 ? wave % A_LOADS : A_LOADS + wave + WAVES * (j - 1);
+    else return wave + WAVES * j;
+  };
   uint32_t ld_voff[LPW];
 #pragma unroll
   for (int j = 0; j < LPW; ++j) {
-    const int ii = wave + WAVES * j;
+    const int ii = piece_of(j);
     if (ii < A_LOADS) {
       const int s = ii * 64 + lane, row = s >> 2, chunk = (s & 3) ^ ((row >> 2) & 3);
       ld_voff[j] = (uint32_t)min(row, T - 1 - m0) * pitch + (uint32_t)chunk * 16;
@@ -123,7 +134,7 @@ __global__ __launch_bounds__(128 * WNW, 2) void ffn_gate_up_kernel(const bf16_t*
   auto produce_piece = [&](int j) __attribute__((always_inline)) {
     if (pt >= n_slices) return;
     const uint32_t stage = __builtin_amdgcn_readfirstlane(smem_base + (uint32_t)(pt % NSTAGE) * STAGE_BYTES);
-    const int ii = wave + WAVES * j;
+    const int ii = piece_of(j);
     dma16s(ii < A_LOADS ? a_base + (size_t)pt * (BK * 2) : b_base + (size_t)pt * 16384, ld_voff[j], stage + (uint32_t)ii * 1024);
     if (j == LPW - 1) ++pt;
   };
@@ -175,7 +186,8 @@ __global__ __launch_bounds__(128 * WNW, 2) void ffn_gate_up_kernel(const bf16_t*
   // this wave's loads of slice s are done when at most (slices issued after it) * LPW remain
   auto wait_slice = [&](int s) __attribute__((always_inline)) {
     const int later = pt - s - 1;
-    if (NSTAGE > 5 && later >= 4) SPD_WAIT_VMCNT(4 * LPW);
+    if (NSTAGE > 6 && later >= 5) SPD_WAIT_VMCNT(5 * LPW);
+    else if (NSTAGE > 5 && later >= 4) SPD_WAIT_VMCNT(4 * LPW);
     else if (NSTAGE > 4 && later == 3) SPD_WAIT_VMCNT(3 * LPW);
     else if (later >= 2) SPD_WAIT_VMCNT(2 * LPW);
     else if (later == 1) SPD_WAIT_VMCNT(LPW);
@@ -265,7 +277,13 @@ hipError_t launch_ffn_gate_up(const void* x, const void* w_gu, void* out, int T,
   // small batches are bound by reading the weights: the small tile where the large one would leave
   // half of the share's compute units without a workgroup
   const int large_tiles = ((T + 255) / 256) * (2 * I / 256);
-  if (T <= 64) return launch_tiles<1, 2, 6>(x, w_gu, out, T, K, I, xcds, stream);
+  if (T <= 64) {
+    // 64 x 256 tiles (one workgroup per CU, 96 KiB of weights in flight) where they give nearly every compute
+    // unit of the share a workgroup; 64 x 128 tiles (two per CU, 80 KiB in flight) otherwise
+    const int wide_tiles = 2 * I / 256;
+    if (8 * wide_tiles >= 7 * cus) return launch_tiles<1, 4, 7>(x, w_gu, out, T, K, I, xcds, stream);
+    return launch_tiles<1, 2, 6>(x, w_gu, out, T, K, I, xcds, stream);
+  }
   if (T <= 128 || (T <= 256 && 2 * large_tiles <= cus)) return launch_tiles<2, 2, 4>(x, w_gu, out, T, K, I, xcds, stream);
   return launch_tiles<4, 4, 4>(x, w_gu, out, T, K, I, xcds, stream);
 }

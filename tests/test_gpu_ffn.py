@@ -59,6 +59,34 @@ def test_gate_up_matches_oracle(T, K, I):
     ctx.close()
 
 
+@pytest.mark.parametrize("T,K,I", [(1, 256, 128), (7, 512, 384), (31, 256, 640), (32, 1024, 128), (33, 256, 128), (48, 768, 256),
+                                   (63, 512, 128), (64, 256, 384), (16, 4096, 256), (64, 4096, 128)])
+def test_gate_up_batches_of_up_to_64_tokens(T, K, I):
+    """At most 64 tokens: the small-tile instances (which one depends on the phase's share of compute units and on
+    inter), ragged token counts, 8 to 128 slices."""
+    ctx = S.Context(0)
+    xb, wgb, wub = W.ffn_inputs(T, K, I, seed=500 + T)
+    for phase in (PRE, DEC):
+        out, _ = _run(ctx, phase, xb, wgb, wub)
+        _assert_ffn(host_f64(out), F.gate_up(f64(xb), f64(wgb), f64(wub)), f"ffn small batch T={T} K={K} I={I}")
+    ctx.close()
+
+
+@pytest.mark.parametrize("T,K", [(5, 256), (33, 512), (64, 1024)])
+def test_gate_up_small_batch_on_a_small_share_takes_the_wide_tile(T, K):
+    """inter = 3584 gives 28 tiles of 256 joint columns: on a 32-CU decode share that is enough for the 64 x 256
+    instance (eight waves, one piece of x per wave), which the shapes above never reach on larger shares."""
+    ctx = S.Context(0)
+    total, _, gran = ctx.device_info()
+    ctx.set_partition(total - gran, gran)
+    I = 3584
+    xb, wgb, wub = W.ffn_inputs(T, K, I, seed=900 + T)
+    out, _ = _run(ctx, DEC, xb, wgb, wub)
+    assert ctx.get_partition()[1] == gran
+    _assert_ffn(host_f64(out), F.gate_up(f64(xb), f64(wgb), f64(wub)), f"ffn small batch, wide tile T={T} K={K}")
+    ctx.close()
+
+
 def test_both_phases_and_partitions_give_the_same_bits():
     ctx = S.Context(0)
     total = ctx.device_info()[0]
