@@ -566,6 +566,27 @@ def main():
                 sub8["unit"] = result["unit"]
                 sub8["config"]["kv_cache"] = "fp8 e4m3, one fp32 scale per 128 latent entries, rope entries bf16"
                 result["configs"][other.name + "_fp8kv"] = sub8
+        if cfg.name == "c2_llama3_8b":
+            # config 5: the dynamic trace (2000 requests, Poisson 8/s, resize 40/60 -> 60/40 mid-run) replayed over a
+            # 40 GB pool of the same layer shape; a failure is reported in the line, it does not take the line away
+            try:
+                import torch
+                from paper_2504_19867_amd.trace_replay import replay
+                torch.cuda.empty_cache()
+                tr = W.trace(2000, 8.0)
+                st, _, _, _ = replay(cfg.layer, tr.arrival_s, tr.input_len, tr.output_len, 40_000_000_000 // cfg.layer.page_bytes)
+                result["configs"]["c5_dynamic_trace"] = {
+                    "requests": st["requests"], "wall_s": st["wall_s"], "time_scale": st["time_scale"],
+                    "prefill_tok_s": st["prefill_tok_s"], "decode_tok_s": st["decode_tok_s"],
+                    "prefill_step_ms_p50": st["prefill_step_ms"]["p50"], "decode_step_ms_p50": st["decode_step_ms"]["p50"],
+                    "decode_batch_mean": st["decode_batch"].get("mean"), "decode_batch_p50": st["decode_batch"]["p50"],
+                    "resize": {k: st["resize"][k] for k in ("from", "to", "set_partition_call_ms", "active_cus_after",
+                                                            "first_prefill_step_after_ms", "first_decode_step_after_ms")},
+                    "preemptions": st["pool"]["preemptions"], "peak_used_pages": st["pool"]["peak_used_pages"],
+                    "decode_outputs_finite": st["decode_outputs_finite"],
+                    "unit": "step times from the phases' own events; tokens/s = tokens of the steps / summed step times"}
+            except Exception as e:          # noqa: BLE001 (whatever it is, it goes into the line)
+                result["configs"]["c5_dynamic_trace"] = {"error": repr(e)}
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cfg, r)
     print(json.dumps(result))
