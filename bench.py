@@ -58,6 +58,8 @@ def parse():
                     help="profiling aid: skip the solo passes, so that every launch of the run is in the headline regime")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="profiling aid: also run a plain 1 GiB copy kernel four times (known traffic for the byte counters)")
+    ap.add_argument("--fp8-kv", action="store_true",
+                    help="profiling aid: run the headline passes of an MLA config over the FP8 latent cache")
     ap.add_argument("--pool-gb", type=float, default=None, help="override pool size (GB)")
     ap.add_argument("--no-scramble", action="store_true", help="experiment: hand out physical pages in order")
     ap.add_argument("--decode-per-prefill", type=int, default=0,
@@ -538,7 +540,7 @@ def main():
         sys.exit(2)
     import workloads as W
     cfg = W.get_config(args.config)
-    part, r = measure_config(cfg, args, args.steps, args.warmup, not args.no_sweep, not args.no_clock)
+    part, r = measure_config(cfg, args, args.steps, args.warmup, not args.no_sweep, not args.no_clock, fp8=args.fp8_kv)
     result = {
         "metric": "prefill tok/s + decode tok/s at CU split; % MFMA peak / % HBM BW",
         "value": part.pop("value"),
