@@ -128,13 +128,34 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     slot_of(j, row, coff, pitch);
     ld_voff[j] = (uint32_t)row * pitch + (uint32_t)coff;
   }
+  // ---- the chain's work items, 64 at a time, one per lane: item i sits in lane i - dsc_base.  An item is then had
+  // with six lane reads, where a load from memory at every item boundary (one by the producer, one by the
+  // compute side, each waited for at once, and every such wait also drains the tile loads in flight) cost the
+  // chain about as much as three tiles.  The producer is at most a few items ahead of the compute side, which
+  // moves the window when it is half way through it.  (Not with 192 dims: no six registers are left there.)
+  constexpr bool ITEM_LANES = DQK <= 128;
+  int dsc_base = it;
+  int d_row0 = 0, d_len = 0, d_qtile = 0, d_head0 = 0, d_kvrow0 = 0, d_qoff = 0;
+  auto load_items = [&](int base) __attribute__((always_inline)) {
+    const PrefillWork pw = work[min(base + lane, it_end - 1)];
+    d_row0 = pw.row0; d_len = pw.len; d_qtile = pw.q_tile; d_head0 = pw.head0; d_kvrow0 = pw.kv_row0; d_qoff = pw.q_off;
+    dsc_base = base;
+  };
+  auto item_of = [&](int i) __attribute__((always_inline)) -> PrefillWork {
+    if constexpr (!ITEM_LANES) return work[i];
+    const int l = i - dsc_base;
+    return PrefillWork{__builtin_amdgcn_readlane(d_row0, l), __builtin_amdgcn_readlane(d_len, l),
+                       __builtin_amdgcn_readlane(d_qtile, l), __builtin_amdgcn_readlane(d_head0, l),
+                       __builtin_amdgcn_readlane(d_kvrow0, l), __builtin_amdgcn_readlane(d_qoff, l)};
+  };
+  if constexpr (ITEM_LANES) load_items(it);
   // ---- producer: the tile loads run ahead of the compute (a pair of tiles, or PD tiles where the
   // ring has three stages), across the items of the chain.
   // pt counts the tiles issued so far (tile number pt goes to stage pt % NSTAGE).
   int p_it = it, p_kt = 0, p_n = 0, p_kv_len = 0, pt = 0;
   const char *p_kb = nullptr, *p_vb = nullptr;
   auto producer_item = [&]() {                  // producer state for item p_it
-    const PrefillWork pw = work[p_it];
+    const PrefillWork pw = item_of(p_it);
     const int pg = pw.head0 / G;
     p_kv_len = pw.q_off + pw.len;
     const int kv_end = min(p_kv_len, pw.q_off + pw.q_tile * (32 * QS) + 32 * QS);
@@ -223,8 +244,24 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
   bf16x8 qf[KS];                                // Q^T fragments (B operand: column = query, 8 consecutive dims per lane and k-step)
   f32x16 O[VB];
   float m = 0.f, l = 0.f;
+  // The next item's query rows are touched ahead of time, one 128-byte line per lane, so that its fragment loads,
+  // which nothing can overlap (every wave of the workgroup stands at the same item boundary), find them in the L2
+  // instead of in HBM.  The touch goes out behind the first full wait of the item (a pair's barrier), so that it
+  // has two tiles' time before the next one; the loaded word is never used, its register passes every full wait.
+  uint32_t q_touch = 0;
+  bool touch_next = false;
+  auto touch_next_q = [&]() __attribute__((always_inline)) {
+    const PrefillWork w2 = item_of(it + 1);
+    constexpr int LINES = DQK / 64;               // 128-byte lines per query row
+    int r2 = w2.q_tile * (32 * QS) + 32 * (wave / HB) + lane / LINES;
+    r2 = r2 < w2.len ? r2 : w2.len - 1;
+    const char* p2 = (const char*)(q + ((size_t)(w2.row0 + r2) * H + w2.head0 + wave % HB) * DQK) + (lane % LINES) * 128;
+    asm volatile("global_load_dword %0, %1, off" : "=v"(q_touch) : "v"(p2) : "memory");
+    touch_next = false;
+  };
   auto item_begin = [&]() {
-    w = work[it];
+    if (ITEM_LANES && it - dsc_base >= 32) load_items(it);      // (the producer is past `it` and less than 32 items ahead)
+    w = item_of(it);
     h = w.head0 + wave % HB;
     const int q_start = w.q_tile * (32 * QS);
     wave_q0 = q_start + 32 * (wave / HB);
@@ -250,6 +287,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
     // use, inside the tile, with a count that knows nothing of the tile loads issued by hand.
 #pragma unroll
     for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(__builtin_bit_cast(uint4, qf[s]).x));
+    touch_next = ITEM_LANES && it + 1 < it_end;
   };
   auto item_end = [&]() {
     l += __shfl_xor(l, 32);
@@ -289,8 +327,10 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
       // with the pair before, whose two stages are refilled, one now and one a tile later.
       if ((ST & 1) == 0) {
         SPD_WAIT_VMCNT(0);
+        asm volatile("" : "+v"(q_touch));
         asm volatile("s_barrier" ::: "memory");
         produce_one();
+        if (touch_next) touch_next_q();
       } else {
         produce_one();                          // the pair's second tile a tile later: eight loads at once queue up
       }

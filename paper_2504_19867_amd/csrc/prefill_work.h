@@ -12,13 +12,17 @@ namespace spd {
 // (round-robin dispatch), and each XCD has its own L2, so all items that read the same K, V - the
 // query tiles and head groups of one (request, KV head) "unit" - go to chains of the same XCD.
 // Units are spread over the XCDs longest-first; inside an XCD the items are dealt longest-first onto
-// the least-loaded chain (weight = KV tiles to visit + a fixed per-item cost), and every chain is
+// the least-loaded chain (weight = KV tiles to visit + a fixed per-item cost: measured, an item costs what
+// four tiles cost beyond its own, in query loads, output stores and a first tile that sets the softmax
+// reference), and every chain is
 // ordered by unit, so that the chains of an XCD work on the same unit at about the same time.
 // With fewer units than XCDs the items themselves are dealt round-robin.
 // n_blocks == 0 asks for one workgroup per item instead (chains of length one, handed out by the
 // hardware in launch order: the XCDs' queues interleaved, each queue heaviest unit first): for
 // partitions on which a launch of exactly one workgroup per compute unit does not get one compute
 // unit each.
+constexpr long ITEM_COST_TILES = 4;
+
 inline void build_prefill_chains(const int32_t* cu_seqlens, const int32_t* prefix_lens, const int32_t* kv_cu, int n_req,
                                  int H, int Hkv, int xcds, int n_blocks, std::vector<PrefillWork>& work,
                                  std::vector<int32_t>& chain) {
@@ -35,8 +39,8 @@ inline void build_prefill_chains(const int32_t* cu_seqlens, const int32_t* prefi
       for (int t = tiles - 1; t >= 0; --t)
         for (int hg = 0; hg < groups; ++hg) {
           const long kv_tiles = (q_off + std::min<long>(len, (long)(t + 1) * bm) + 63) / 64;
-          u.items.push_back(Item{PrefillWork{row0, len, t, g * G + hg * hb, kv_row0, q_off}, kv_tiles + 1, (int)units.size()});
-          u.weight += kv_tiles + 1;
+          u.items.push_back(Item{PrefillWork{row0, len, t, g * G + hg * hb, kv_row0, q_off}, kv_tiles + ITEM_COST_TILES, (int)units.size()});
+          u.weight += kv_tiles + ITEM_COST_TILES;
         }
       units.push_back(std::move(u));
     }
