@@ -132,7 +132,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
   // with six lane reads, where a load from memory at every item boundary (one by the producer, one by the
   // compute side, each waited for at once, and every such wait also drains the tile loads in flight) cost the
   // chain about as much as three tiles.  The producer is at most a few items ahead of the compute side, which
-  // moves the window when it is half way through it.  (Not with 192 dims: no six registers are left there.)
+  // moves the window when it is half way through it.  (Not with 192 dims: the touch below needs the full wait that
+  // only the paired tiles have.)
   constexpr bool ITEM_LANES = DQK <= 128;
   int dsc_base = it;
   int d_row0 = 0, d_len = 0, d_qtile = 0, d_head0 = 0, d_kvrow0 = 0, d_qoff = 0;
@@ -422,7 +423,9 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(const bf16_t* __restric
         }
       return (ls[0] + ls[1]) + (ls[2] + ls[3]);
     };
-    float psum = softmax_p(m * c);
+    // (an item's first tile has no reference yet: the pass against it would be thrown away, so it is not made)
+    float psum = INFINITY;
+    if (kt != 0) psum = softmax_p(m * c);
     if (__builtin_amdgcn_ballot_w64(!(psum < 0x1p60f)) != 0) {
       float mx = S[0][0];
 #pragma unroll
